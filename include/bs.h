@@ -1,0 +1,131 @@
+/*
+ * bs.h -- C ABI of the Balanced-Sparsity multiply library for AMD MI355X (gfx950).
+ *
+ * Method: arXiv 1811.00206, "Balanced Sparsity for Efficient DNN Inference on
+ * GPU".  A weight matrix W (M x K, row-major) is stored in Balanced-Sparsity
+ * form (Sec. 3.1): every row is cut into K/bank contiguous blocks of `bank`
+ * elements (the paper's "balance range"; called banks here) and every bank
+ * keeps exactly `k` weights, the k largest in absolute value (Sec. 3.2,
+ * Algorithm 1).  The packed matrix is two arrays in the layout [M][K/bank][k]:
+ *
+ *   vals  the kept weights, bit copies of the elements of W (fp32 or binary16)
+ *   idx   their offsets inside the bank, one byte each (0 .. bank-1),
+ *         strictly ascending inside a bank
+ *
+ * so the column of entry (r, j, t) is j*bank + idx[r][j][t] (Fig. 3: the dense
+ * vector is read "according to the indexes").  Ties in |w| keep the lower
+ * offset, which makes vals/idx unique for a given W.
+ *
+ * Conventions of every call
+ *   - Pointers marked DEVICE are device pointers owned by the caller; the
+ *     library neither allocates nor frees nor keeps them.  A `workspace` is
+ *     caller-owned device memory too.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls only enqueue work on it; they never synchronise.
+ *   - Outputs are fully overwritten; they need no initialisation.
+ *   - Base pointers of W, vals, idx, x, X, y, Y must be 16-byte aligned.
+ *   - Arguments are validated on the host before anything is launched; a
+ *     non-zero return means nothing was enqueued.
+ *   - NaN or Inf inside W is undefined behaviour for bs_prune_pack.
+ *   - Requires: bank in 1..256, K % bank == 0, 1 <= k <= bank, M >= 1,
+ *     M*K < 2^40, K <= 2^24.
+ */
+#ifndef BS_H
+#define BS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BS_OK = 0,
+    BS_ERR_NULL = 1,        /* a required pointer is NULL                         */
+    BS_ERR_SHAPE = 2,       /* K % bank != 0, k < 1, k > bank, M/K/N < 1, ld < N  */
+    BS_ERR_UNSUPPORTED = 3, /* bank > 256, unknown dtype, size over a stated limit */
+    BS_ERR_ALIGN = 4,       /* a base pointer is not 16-byte aligned              */
+    BS_ERR_HIP = 5,         /* the HIP runtime refused the launch                 */
+    BS_ERR_WORKSPACE = 6    /* workspace missing or smaller than required         */
+} bs_status;
+
+/* storage type of W and vals; x, X, y, Y and all accumulation are fp32 */
+typedef enum { BS_F32 = 0, BS_F16 = 1 } bs_dtype;
+
+/* ---- sizes (host only, no GPU needed) ----------------------------------- */
+
+/* number of stored entries M*(K/bank)*k; 0 if the shape is invalid */
+size_t bs_nnz(int64_t M, int64_t K, int bank, int k);
+/* bytes of vals / idx for that shape; 0 if the shape or dtype is invalid */
+size_t bs_vals_bytes(int64_t M, int64_t K, int bank, int k, int dtype);
+size_t bs_idx_bytes(int64_t M, int64_t K, int bank, int k);
+
+/* text for a bs_status value (static storage) */
+const char* bs_status_str(int status);
+
+/* ---- prune + pack: Sec. 3.1 pattern, Sec. 3.2 / Algorithm 1 selection ---- */
+
+/*
+ * W      DEVICE in   M x K row-major, contiguous, fp32 (BS_F32) or binary16 (BS_F16)
+ * vals   DEVICE out  [M][K/bank][k], same element type as W, bit copies
+ * idx    DEVICE out  [M][K/bank][k] bytes
+ * One-shot pruning to k per bank; identical to running Algorithm 1's loop
+ * without retraining, since zeroing the smallest never reorders the rest.
+ */
+int bs_prune_pack(const void* W, int dtype, int64_t M, int64_t K, int bank, int k,
+                  void* vals, uint8_t* idx, void* stream);
+
+/* ---- y = W_sparse . x  (Sec. 3.4, batch size 1; eq. (1) with zero bias) --- */
+
+/*
+ * vals, idx  DEVICE in   packed matrix as written by bs_prune_pack
+ * x          DEVICE in   K fp32
+ * y          DEVICE out  M fp32;  y[r] = sum_j sum_t vals[r][j][t] * x[j*bank + idx[r][j][t]]
+ * fp32 multiply-add, fp32 accumulation (binary16 vals are widened exactly).
+ * The summation order is fixed for a given shape, so results are
+ * bit-reproducible from call to call.
+ */
+int bs_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K,
+            int bank, int k, const float* x, float* y, void* stream);
+
+/*
+ * Same product with an explicit launch shape, for tuning sweeps.
+ *   lanes_per_row  lanes of one wavefront that share a row: 1,2,4,...,64;
+ *                  0 = choose from the shape (what bs_spmv does)
+ *   rows_per_wg    rows handled by one workgroup; lanes_per_row*rows_per_wg must
+ *                  be a multiple of 64 and at most 1024; 0 = choose
+ * Invalid combinations return BS_ERR_UNSUPPORTED.
+ */
+int bs_spmv_ex(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K,
+               int bank, int k, const float* x, float* y,
+               int lanes_per_row, int rows_per_wg, void* stream);
+
+/* ---- Y = W_sparse . X  (Sec. 3.4 / Sec. 4.1, batch size > 1; im2col conv) - */
+
+/*
+ * X   DEVICE in   K x N fp32 row-major, leading dimension ldx >= N
+ * Y   DEVICE out  M x N fp32 row-major, leading dimension ldy >= N
+ * Y[r][n] = sum_j sum_t vals[r][j][t] * X[j*bank + idx[r][j][t]][n]
+ * workspace / workspace_bytes: DEVICE scratch of at least
+ * bs_spmm_workspace_bytes(...) bytes (may be NULL when that is 0).
+ */
+size_t bs_spmm_workspace_bytes(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N);
+int bs_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K,
+            int bank, int k, const float* X, int64_t N, int64_t ldx,
+            float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- dense baseline the sparse path is compared with (Sec. 4: the paper's
+ *      dense column; here a hand-written kernel on the same GPU) ----------- */
+
+/* y = W . x over all K columns; W M x K row-major fp32 or binary16; fp32 accumulate */
+int bs_dense_gemv(const void* W, int dtype, int64_t M, int64_t K,
+                  const float* x, float* y, void* stream);
+/* Y = W . X;  X K x N (ldx), Y M x N (ldy), fp32 */
+int bs_dense_gemm(const void* W, int dtype, int64_t M, int64_t K,
+                  const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BS_H */

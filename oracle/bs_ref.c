@@ -1,0 +1,351 @@
+/*
+ * bs_ref.c -- CPU oracle for the Balanced-Sparsity hot path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU library is checked against.  It shares no code, header, table or helper
+ * with the HIP path, and nothing in the product may call it: only tests/,
+ * the smoke check and the bench's cpu_baseline leg do.
+ *
+ * What it follows (arXiv 1811.00206, "Balanced Sparsity for Efficient DNN
+ * Inference on GPU"):
+ *   - Sec. 3.1: every matrix row is cut into equal-size blocks ("banks" here,
+ *     length B = the paper's balance range) and every bank keeps the same
+ *     number k of weights.
+ *   - Sec. 3.2 / Algorithm 1 (final pruning step): inside each bank the weights
+ *     are ordered by absolute magnitude and the smallest are zeroed.
+ *   - Fig. 3: the multiply reads the dense vector "according to the indexes",
+ *     i.e. position = bank base + offset inside the bank.
+ *   - Eq. (1)/(2): the layer output is W.X with zero bias, so the sparse
+ *     product must equal the dense product of the pruned matrix.
+ *
+ * Readings taken where the paper is silent:
+ *   - exactly k stored slots per bank (Algorithm 1's strict "< T" test would
+ *     keep every element tied with T and break Sec. 3.1's equal count);
+ *     among equal magnitudes the LOWER offset is kept; +a and -a tie.
+ *   - kept entries are stored in ascending offset; values are bit copies.
+ *   - offsets are bytes, so B <= 256; K must be a multiple of B.
+ *   - NaN/Inf in W, x or X: rejected (BS_REF_ERR_NONFINITE).
+ *
+ * Arithmetic: every product and sum is done in double; one rounding to float
+ * at the end.  No blocking, no reordering: rows ascending, banks ascending,
+ * slots ascending.
+ *
+ * All pointers are HOST pointers.
+ */
+#include <math.h>
+#include <pthread.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum {
+    BS_REF_OK = 0,
+    BS_REF_ERR_NULL = 1,
+    BS_REF_ERR_SHAPE = 2,
+    BS_REF_ERR_NONFINITE = 6
+};
+
+/* ---------- shape checks ------------------------------------------------ */
+
+static int shape_ok(int64_t M, int64_t K, int B, int k)
+{
+    if (M < 1 || K < 1 || B < 1 || B > 256 || k < 1 || k > B) return 0;
+    if (K % B != 0) return 0;
+    return 1;
+}
+
+/* ---------- IEEE binary16 decode, written out ---------------------------- */
+
+/* value of a binary16 bit pattern as a double; NaN/Inf come back as such */
+static double half_bits_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int expo = (h >> 10) & 0x1f;
+    int mant = h & 0x3ff;
+    double v;
+    if (expo == 0)
+        v = ldexp((double)mant, -24);               /* zero / subnormal */
+    else if (expo == 31)
+        v = mant ? NAN : INFINITY;
+    else
+        v = ldexp((double)(mant + 1024), expo - 25); /* 1.m * 2^(e-15) */
+    return sign ? -v : v;
+}
+
+/* ---------- prune + pack (Sec. 3.1, Sec. 3.2 / Algorithm 1) -------------- */
+
+/*
+ * One bank: mag[0..B) are the magnitudes.  keep[o] = 1 iff fewer than k
+ * elements precede o in the order "larger magnitude first, lower offset first
+ * among equals".  Brute force, O(B^2).
+ */
+static void bank_select(const double *mag, int B, int k, unsigned char *keep)
+{
+    for (int o = 0; o < B; ++o) {
+        int rank = 0;
+        for (int p = 0; p < B; ++p) {
+            if (mag[p] > mag[o]) ++rank;
+            else if (mag[p] == mag[o] && p < o) ++rank;
+        }
+        keep[o] = (rank < k);
+    }
+}
+
+int bs_ref_prune_pack_f32(const float *W, int64_t M, int64_t K, int B, int k,
+                          float *vals, uint8_t *idx)
+{
+    if (!W || !vals || !idx) return BS_REF_ERR_NULL;
+    if (!shape_ok(M, K, B, k)) return BS_REF_ERR_SHAPE;
+    int64_t nb = K / B;
+    double mag[256];
+    unsigned char keep[256];
+    for (int64_t r = 0; r < M; ++r) {
+        for (int64_t j = 0; j < nb; ++j) {
+            const float *bank = W + r * K + j * B;
+            for (int o = 0; o < B; ++o) {
+                if (!isfinite(bank[o])) return BS_REF_ERR_NONFINITE;
+                mag[o] = fabs((double)bank[o]);
+            }
+            bank_select(mag, B, k, keep);
+            int64_t out = (r * nb + j) * k;
+            int t = 0;
+            for (int o = 0; o < B; ++o) {
+                if (keep[o]) {
+                    memcpy(&vals[out + t], &bank[o], sizeof(float));
+                    idx[out + t] = (uint8_t)o;
+                    ++t;
+                }
+            }
+            if (t != k) return BS_REF_ERR_SHAPE; /* cannot happen */
+        }
+    }
+    return BS_REF_OK;
+}
+
+/* binary16 storage: W and vals are raw 16-bit patterns */
+int bs_ref_prune_pack_f16(const uint16_t *W, int64_t M, int64_t K, int B, int k,
+                          uint16_t *vals, uint8_t *idx)
+{
+    if (!W || !vals || !idx) return BS_REF_ERR_NULL;
+    if (!shape_ok(M, K, B, k)) return BS_REF_ERR_SHAPE;
+    int64_t nb = K / B;
+    double mag[256];
+    unsigned char keep[256];
+    for (int64_t r = 0; r < M; ++r) {
+        for (int64_t j = 0; j < nb; ++j) {
+            const uint16_t *bank = W + r * K + j * B;
+            for (int o = 0; o < B; ++o) {
+                double v = half_bits_to_double(bank[o]);
+                if (!isfinite(v)) return BS_REF_ERR_NONFINITE;
+                mag[o] = fabs(v);
+            }
+            bank_select(mag, B, k, keep);
+            int64_t out = (r * nb + j) * k;
+            int t = 0;
+            for (int o = 0; o < B; ++o) {
+                if (keep[o]) {
+                    vals[out + t] = bank[o];
+                    idx[out + t] = (uint8_t)o;
+                    ++t;
+                }
+            }
+            if (t != k) return BS_REF_ERR_SHAPE;
+        }
+    }
+    return BS_REF_OK;
+}
+
+/* ---------- unpack: the pruned dense matrix M_p of Algorithm 1 ----------- */
+
+int bs_ref_unpack_f32(const float *vals, const uint8_t *idx, int64_t M, int64_t K,
+                      int B, int k, float *Wp)
+{
+    if (!vals || !idx || !Wp) return BS_REF_ERR_NULL;
+    if (!shape_ok(M, K, B, k)) return BS_REF_ERR_SHAPE;
+    int64_t nb = K / B;
+    memset(Wp, 0, (size_t)(M * K) * sizeof(float));
+    for (int64_t r = 0; r < M; ++r)
+        for (int64_t j = 0; j < nb; ++j)
+            for (int t = 0; t < k; ++t) {
+                int64_t e = (r * nb + j) * k + t;
+                if (idx[e] >= B) return BS_REF_ERR_SHAPE;
+                memcpy(&Wp[r * K + j * B + idx[e]], &vals[e], sizeof(float));
+            }
+    return BS_REF_OK;
+}
+
+int bs_ref_unpack_f16(const uint16_t *vals, const uint8_t *idx, int64_t M, int64_t K,
+                      int B, int k, uint16_t *Wp)
+{
+    if (!vals || !idx || !Wp) return BS_REF_ERR_NULL;
+    if (!shape_ok(M, K, B, k)) return BS_REF_ERR_SHAPE;
+    int64_t nb = K / B;
+    memset(Wp, 0, (size_t)(M * K) * sizeof(uint16_t));
+    for (int64_t r = 0; r < M; ++r)
+        for (int64_t j = 0; j < nb; ++j)
+            for (int t = 0; t < k; ++t) {
+                int64_t e = (r * nb + j) * k + t;
+                if (idx[e] >= B) return BS_REF_ERR_SHAPE;
+                Wp[r * K + j * B + idx[e]] = vals[e];
+            }
+    return BS_REF_OK;
+}
+
+/* ---------- sparse products (Fig. 3; eq. (1) with zero bias) ------------- */
+
+/*
+ * One output element in double:
+ *   sum_j sum_t vals[r][j][t] * X[j*B + idx[r][j][t]][n]
+ * banks ascending, slots ascending.  is_f16 selects the storage type of vals.
+ * X is K x N row-major with leading dimension ldx.
+ */
+static int row_dot_f64(const void *vals, int is_f16, const uint8_t *idx,
+                       int64_t K, int B, int k, const float *X, int64_t ldx,
+                       int64_t r, int64_t n, double *out)
+{
+    int64_t nb = K / B;
+    double acc = 0.0;
+    for (int64_t j = 0; j < nb; ++j) {
+        for (int t = 0; t < k; ++t) {
+            int64_t e = (r * nb + j) * k + t;
+            double w = is_f16 ? half_bits_to_double(((const uint16_t *)vals)[e])
+                              : (double)((const float *)vals)[e];
+            if (idx[e] >= B) return BS_REF_ERR_SHAPE;
+            double xv = (double)X[(j * B + idx[e]) * ldx + n];
+            if (!isfinite(w) || !isfinite(xv)) return BS_REF_ERR_NONFINITE;
+            acc += w * xv;
+        }
+    }
+    *out = acc;
+    return BS_REF_OK;
+}
+
+static int spmm_check(const void *vals, const uint8_t *idx, int64_t M, int64_t K,
+                      int B, int k, const float *X, int64_t N, int64_t ldx,
+                      const void *Y, int64_t ldy)
+{
+    if (!vals || !idx || !X || !Y) return BS_REF_ERR_NULL;
+    if (!shape_ok(M, K, B, k)) return BS_REF_ERR_SHAPE;
+    if (N < 1 || ldx < N || ldy < N) return BS_REF_ERR_SHAPE;
+    return BS_REF_OK;
+}
+
+/* double-precision outputs: the un-rounded sums (used by the exactness pins) */
+int bs_ref_spmm_f64(const void *vals, int is_f16, const uint8_t *idx, int64_t M,
+                    int64_t K, int B, int k, const float *X, int64_t N,
+                    int64_t ldx, double *Yd, int64_t ldy)
+{
+    int st = spmm_check(vals, idx, M, K, B, k, X, N, ldx, Yd, ldy);
+    if (st) return st;
+    for (int64_t r = 0; r < M; ++r)
+        for (int64_t n = 0; n < N; ++n) {
+            st = row_dot_f64(vals, is_f16, idx, K, B, k, X, ldx, r, n, &Yd[r * ldy + n]);
+            if (st) return st;
+        }
+    return BS_REF_OK;
+}
+
+/* ---- row-split threading: rows are independent, per-row arithmetic is the
+ *      same code, so the result is identical for any thread count ---------- */
+
+typedef struct {
+    const void *vals; int is_f16; const uint8_t *idx;
+    int64_t K; int B; int k;
+    const float *X; int64_t N; int64_t ldx;
+    float *Y; int64_t ldy; int64_t r0; int64_t r1; int status;
+} spmm_job;
+
+static void *spmm_job_run(void *arg)
+{
+    spmm_job *jb = (spmm_job *)arg;
+    jb->status = BS_REF_OK;
+    for (int64_t r = jb->r0; r < jb->r1; ++r)
+        for (int64_t n = 0; n < jb->N; ++n) {
+            double acc;
+            int st = row_dot_f64(jb->vals, jb->is_f16, jb->idx, jb->K, jb->B, jb->k,
+                                 jb->X, jb->ldx, r, n, &acc);
+            if (st) { jb->status = st; return NULL; }
+            jb->Y[r * jb->ldy + n] = (float)acc; /* the single rounding */
+        }
+    return NULL;
+}
+
+/*
+ * Y = fp32( W_sparse . X ), accumulated in double.  threads <= 1 runs inline.
+ */
+int bs_ref_spmm(const void *vals, int is_f16, const uint8_t *idx, int64_t M,
+                int64_t K, int B, int k, const float *X, int64_t N, int64_t ldx,
+                float *Y, int64_t ldy, int threads)
+{
+    int st = spmm_check(vals, idx, M, K, B, k, X, N, ldx, Y, ldy);
+    if (st) return st;
+    if (threads < 1) threads = 1;
+    if (threads > 256) threads = 256;
+    if ((int64_t)threads > M) threads = (int)M;
+    spmm_job jobs[256];
+    pthread_t tid[256];
+    for (int t = 0; t < threads; ++t) {
+        spmm_job jb = { vals, is_f16, idx, K, B, k, X, N, ldx, Y, ldy,
+                        M * t / threads, M * (t + 1) / threads, 0 };
+        jobs[t] = jb;
+    }
+    if (threads == 1) {
+        spmm_job_run(&jobs[0]);
+        return jobs[0].status;
+    }
+    for (int t = 0; t < threads; ++t)
+        if (pthread_create(&tid[t], NULL, spmm_job_run, &jobs[t]) != 0) {
+            for (int u = 0; u < t; ++u) pthread_join(tid[u], NULL);
+            return BS_REF_ERR_NULL;
+        }
+    st = BS_REF_OK;
+    for (int t = 0; t < threads; ++t) {
+        pthread_join(tid[t], NULL);
+        if (jobs[t].status && !st) st = jobs[t].status;
+    }
+    return st;
+}
+
+/* y = fp32( W_sparse . x ): the N = 1 case of the definition above */
+int bs_ref_spmv(const void *vals, int is_f16, const uint8_t *idx, int64_t M,
+                int64_t K, int B, int k, const float *x, float *y, int threads)
+{
+    return bs_ref_spmm(vals, is_f16, idx, M, K, B, k, x, 1, 1, y, 1, threads);
+}
+
+/* ---------- dense product, all K columns in ascending order, double ------ */
+
+/* Yd = Wd . X with Wd a dense M x K matrix (fp32 or binary16 bits) */
+int bs_ref_dense_gemm_f64(const void *Wd, int is_f16, int64_t M, int64_t K,
+                          const float *X, int64_t N, int64_t ldx,
+                          double *Yd, int64_t ldy)
+{
+    if (!Wd || !X || !Yd) return BS_REF_ERR_NULL;
+    if (M < 1 || K < 1 || N < 1 || ldx < N || ldy < N) return BS_REF_ERR_SHAPE;
+    for (int64_t r = 0; r < M; ++r)
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int64_t c = 0; c < K; ++c) {
+                double w = is_f16 ? half_bits_to_double(((const uint16_t *)Wd)[r * K + c])
+                                  : (double)((const float *)Wd)[r * K + c];
+                acc += w * (double)X[c * ldx + n];
+            }
+            Yd[r * ldy + n] = acc;
+        }
+    return BS_REF_OK;
+}
+
+/* ---------- error metric -------------------------------------------------- */
+
+/* ||a - b||_2 / ||b||_2 in double; b is the reference.  0/0 -> 0. */
+double bs_ref_rel_l2(const float *a, const float *b, int64_t n)
+{
+    double num = 0.0, den = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double d = (double)a[i] - (double)b[i];
+        num += d * d;
+        den += (double)b[i] * (double)b[i];
+    }
+    if (den == 0.0) return num == 0.0 ? 0.0 : INFINITY;
+    return sqrt(num / den);
+}

@@ -1,0 +1,326 @@
+"""Pins for the CPU oracle: it is checked against things other than itself
+(invariants the paper fixes, library routines with a different algorithm,
+closed-form special cases, brute force written a second way, the geometry of
+the paper's example) before any GPU result is compared with it.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import bs_ref
+from paper_1811_00206_amd import workloads
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ------------------------------------------------------------------ helpers
+
+def rand_w(M, K, seed, dtype=np.float32, sigma=1.0):
+    return workloads.draw_weights(M, K, sigma, "f16" if dtype == np.float16 else "f32", seed)
+
+
+def argsort_topk(W, bank, k):
+    """Second, independent definition: a stable library sort on -|w| (stable =
+    lower index first among equals), keep the first k, report ascending."""
+    M, K = W.shape
+    nb = K // bank
+    Wb = W.reshape(M, nb, bank)
+    order = np.argsort(-np.abs(Wb.astype(np.float64)), axis=2, kind="stable")[:, :, :k]
+    off = np.sort(order, axis=2)
+    vals = np.take_along_axis(Wb, off, axis=2)
+    return vals, off.astype(np.uint8)
+
+
+SHAPES = [(7, 64, 16, 4), (5, 300, 100, 10), (3, 256, 64, 1), (4, 96, 32, 31),
+          (2, 512, 256, 13), (9, 30, 3, 2), (1, 128, 128, 5), (6, 40, 1, 1)]
+
+
+# ------------------------------------------------------------ Sec. 3.1 invariants
+
+@pytest.mark.parametrize("M,K,bank,k", SHAPES)
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_exactly_k_per_bank_and_ascending(M, K, bank, k, dtype):
+    W = rand_w(M, K, 11, dtype)
+    vals, idx = bs_ref.prune_pack(W, bank, k)
+    assert vals.shape == idx.shape == (M, K // bank, k)
+    assert vals.dtype == W.dtype and idx.dtype == np.uint8
+    assert (idx < bank).all()
+    if k > 1:
+        assert (np.diff(idx.astype(np.int32), axis=2) > 0).all()  # strictly ascending
+    # stored values are bit copies of the elements they point at
+    Wb = W.reshape(M, K // bank, bank)
+    picked = np.take_along_axis(Wb, idx.astype(np.int64), axis=2)
+    assert picked.tobytes() == vals.tobytes()
+
+
+@pytest.mark.parametrize("M,K,bank,k", SHAPES)
+def test_kept_are_the_largest_magnitudes(M, K, bank, k):
+    W = rand_w(M, K, 12)
+    vals, idx = bs_ref.prune_pack(W, bank, k)
+    Wb = np.abs(W.reshape(M, K // bank, bank).astype(np.float64))
+    keep = np.zeros_like(Wb, dtype=bool)
+    np.put_along_axis(keep, idx.astype(np.int64), True, axis=2)
+    assert (keep.sum(axis=2) == k).all()
+    if k < bank:
+        kept_min = np.where(keep, Wb, np.inf).min(axis=2)
+        drop_max = np.where(~keep, Wb, -np.inf).max(axis=2)
+        assert (kept_min >= drop_max).all()
+
+
+# ------------------------------------------- independent library definition
+
+@pytest.mark.parametrize("M,K,bank,k", SHAPES)
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_matches_stable_argsort_definition(M, K, bank, k, dtype):
+    W = rand_w(M, K, 13, dtype)
+    vals, idx = bs_ref.prune_pack(W, bank, k)
+    v2, i2 = argsort_topk(W, bank, k)
+    assert np.array_equal(idx, i2)
+    assert vals.tobytes() == np.ascontiguousarray(v2).tobytes()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("levels", [2, 3, 5])
+def test_tie_heavy_matches_stable_argsort(dtype, levels):
+    W = workloads.tie_heavy_weights(16, 256, levels, dtype, 14)
+    for bank, k in [(64, 16), (32, 5), (256, 100), (4, 2)]:
+        vals, idx = bs_ref.prune_pack(W, bank, k)
+        v2, i2 = argsort_topk(W, bank, k)
+        assert np.array_equal(idx, i2)
+        assert vals.tobytes() == np.ascontiguousarray(v2).tobytes()
+
+
+# ------------------------------------------------------------------ tie rule
+
+def test_all_equal_magnitudes_keep_lowest_offsets():
+    bank, k = 16, 5
+    row = np.full(bank, 0.75, dtype=np.float32)
+    row[::2] *= -1  # +a and -a tie
+    vals, idx = bs_ref.prune_pack(row.reshape(1, bank), bank, k)
+    assert idx.ravel().tolist() == [0, 1, 2, 3, 4]
+    assert vals.ravel().tolist() == row[:5].tolist()
+
+
+def test_all_zero_bank_keeps_first_k_slots_and_signed_zero_bits():
+    bank, k = 8, 3
+    row = np.zeros(bank, dtype=np.float32)
+    row[1] = -0.0
+    vals, idx = bs_ref.prune_pack(row.reshape(1, bank), bank, k)
+    assert idx.ravel().tolist() == [0, 1, 2]
+    assert vals.tobytes() == row[:3].tobytes()  # -0.0 survives bit-for-bit
+
+
+def test_k1_is_first_argmax_of_magnitude():
+    W = workloads.tie_heavy_weights(32, 128, 4, "f32", 15)
+    vals, idx = bs_ref.prune_pack(W, 32, 1)
+    expect = np.argmax(np.abs(W.reshape(32, 4, 32)), axis=2)  # numpy: first occurrence
+    assert np.array_equal(idx[:, :, 0], expect)
+
+
+def test_tie_at_the_cut_drops_the_higher_offset():
+    # magnitudes 5 4 3 3 3 1, k = 3 -> keep offsets 0, 1 and the FIRST 3 (offset 2)
+    row = np.array([5, -4, 3, -3, 3, 1], dtype=np.float32)
+    vals, idx = bs_ref.prune_pack(row.reshape(1, 6), 6, 3)
+    assert idx.ravel().tolist() == [0, 1, 2]
+    # and if a larger value sits after the tied ones it is still kept
+    row = np.array([3, -3, 3, 1, 9, 3], dtype=np.float32)
+    vals, idx = bs_ref.prune_pack(row.reshape(1, 6), 6, 3)
+    assert idx.ravel().tolist() == [0, 1, 4]
+    assert vals.ravel().tolist() == [3.0, -3.0, 9.0]
+
+
+def test_subnormals_and_f16_order():
+    # fp16: subnormal < smallest normal; ordering must follow value, not a cast
+    bits = np.array([0x0001, 0x03ff, 0x0400, 0x8002, 0x7bff, 0xfbff, 0x0000, 0x3c00],
+                    dtype=np.uint16)
+    W = bits.view(np.float16).reshape(1, 8)
+    vals, idx = bs_ref.prune_pack(W, 8, 3)
+    assert idx.ravel().tolist() == [4, 5, 7]           # 65504, -65504, 1.0
+    vals, idx = bs_ref.prune_pack(W, 8, 6)
+    assert idx.ravel().tolist() == [1, 2, 3, 4, 5, 7]   # drops 2^-24 and 0
+
+
+# ---------------------------------------------- closed-form special cases
+
+def test_k_equals_bank_is_identity_and_dense_product():
+    M, K, bank = 6, 96, 32
+    W = rand_w(M, K, 16)
+    x = workloads.draw_activations(K, 1, 16)
+    vals, idx = bs_ref.prune_pack(W, bank, bank)
+    assert vals.reshape(M, K).tobytes() == W.tobytes()
+    assert np.array_equal(idx, np.broadcast_to(np.arange(bank, dtype=np.uint8), idx.shape))
+    y = bs_ref.spmv(vals, idx, bank, x)
+    y_np = (W.astype(np.float64) @ x.astype(np.float64))
+    np.testing.assert_allclose(bs_ref.spmm_f64(vals, idx, bank, x), y_np, rtol=1e-12)
+    np.testing.assert_allclose(y, y_np, rtol=2.0 ** -23)   # one fp32 rounding
+
+
+def test_single_bank_per_row_is_row_topk():
+    M, K, k = 5, 200, 17
+    W = rand_w(M, K, 17)
+    vals, idx = bs_ref.prune_pack(W, K, k)
+    for r in range(M):
+        top = np.sort(np.argsort(-np.abs(W[r]), kind="stable")[:k])
+        assert idx[r, 0].tolist() == top.tolist()
+
+
+def test_single_row_and_spmm_n1_equals_spmv():
+    W = rand_w(1, 300, 18)
+    x = workloads.draw_activations(300, 1, 18)
+    vals, idx = bs_ref.prune_pack(W, 100, 10)
+    y = bs_ref.spmv(vals, idx, 100, x)
+    Y = bs_ref.spmm(vals, idx, 100, x.reshape(300, 1))
+    assert y.shape == (1,) and Y.shape == (1, 1)
+    assert y.tobytes() == Y.tobytes()
+
+
+# ------------------------------------- paper's worked example (geometry)
+
+def _golden_geometry():
+    out = {}
+    with open(os.path.join(GOLDEN, "fig2_fig3_geometry.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            key, *rest = line.split()
+            out[key] = [float(v) if "." in v else int(v) for v in rest]
+    return out
+
+
+def test_fig2_fig3_geometry():
+    g = _golden_geometry()
+    K, bank = g["row_length"][0], g["balance_range"][0]
+    nb, k = g["blocks_per_row"][0], g["kept_per_block"][0]
+    assert K == nb * bank and k == round(bank * (1 - g["sparsity"][0]))
+    positions = g["simultaneous_vector_positions"]
+    # a row whose largest entry of block j sits at positions[j], second largest
+    # right after it: 2 survivors per block, first survivor at positions[j]
+    row = np.full(K, 0.01, dtype=np.float32)
+    for j, p in enumerate(positions):
+        assert j * bank <= p < (j + 1) * bank
+        row[p] = 1.0 + j
+        row[p + 1] = -0.5
+    vals, idx = bs_ref.prune_pack(row.reshape(1, K), bank, k)
+    assert vals.shape == (1, nb, k) and vals.size == K // 2
+    first_abs = [j * bank + int(idx[0, j, 0]) for j in range(nb)]
+    assert first_abs == positions            # index = block base + offset
+    # the product really reads the vector at those positions
+    x = np.zeros(K, dtype=np.float32)
+    x[positions] = [1.0, 10.0, 100.0, 1000.0]
+    y = bs_ref.spmv(vals, idx, bank, x)
+    assert y[0] == np.float32(1 * 1 + 2 * 10 + 3 * 100 + 4 * 1000)
+
+
+# ------------------- sparse product == dense product of the pruned matrix
+
+@pytest.mark.parametrize("M,K,bank,k", SHAPES)
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+@pytest.mark.parametrize("N", [1, 5])
+def test_sparse_equals_dense_of_pruned_exactly(M, K, bank, k, dtype, N):
+    W = rand_w(M, K, 19, dtype, sigma=0.05)
+    X = workloads.draw_activations(K, N, 19)
+    vals, idx = bs_ref.prune_pack(W, bank, k)
+    Wp = bs_ref.unpack(vals, idx, bank)
+    # unpack against numpy scatter
+    Wp2 = np.zeros((M, K // bank, bank), dtype=W.dtype)
+    np.put_along_axis(Wp2, idx.astype(np.int64), vals, axis=2)
+    assert Wp.tobytes() == Wp2.reshape(M, K).tobytes()
+    Ys = bs_ref.spmm_f64(vals, idx, bank, X)
+    Yd = bs_ref.dense_gemm_f64(Wp, X)
+    assert np.array_equal(Ys, Yd)            # adding +-0 products changes nothing
+    Ynp = Wp.astype(np.float64) @ X.astype(np.float64)
+    np.testing.assert_allclose(Ys, Ynp, rtol=1e-12, atol=1e-300)
+    # fp32 result is that sum rounded once
+    Y32 = bs_ref.spmm(vals, idx, bank, X)
+    assert np.array_equal(Y32, Ys.astype(np.float32))
+
+
+def test_transposed_or_shifted_operands_would_fail():
+    """Hand-computed product: catches a transposed X, a wrong bank base or a
+    dropped slot in the oracle's indexing."""
+    bank, k = 4, 2
+    # row 0: bank0 keeps offsets 1,3 ; bank1 keeps offsets 0,2
+    vals = np.array([[[2.0, -3.0], [5.0, 7.0]]], dtype=np.float32)
+    idx = np.array([[[1, 3], [0, 2]]], dtype=np.uint8)
+    X = np.arange(16, dtype=np.float32).reshape(8, 2) + 1  # X[c][n] = 2c+n+1
+    Y = bs_ref.spmm(vals, idx, bank, X)
+    # columns: 1, 3, 4, 6 -> X rows [3,4], [7,8], [9,10], [13,14]
+    expect0 = 2 * 3 - 3 * 7 + 5 * 9 + 7 * 13
+    expect1 = 2 * 4 - 3 * 8 + 5 * 10 + 7 * 14
+    assert Y.tolist() == [[float(expect0), float(expect1)]]
+
+
+# -------------------------------------------------- nesting / idempotence
+
+def test_iterative_pruning_equals_one_shot():
+    """Algorithm 1 raises the sparsity step by step; without retraining each
+    step only removes the current smallest, so k' -> k equals one-shot k."""
+    W = rand_w(8, 256, 20)
+    bank = 64
+    for kp, k in [(48, 16), (32, 8), (16, 16), (10, 1)]:
+        v1, i1 = bs_ref.prune_pack(W, bank, kp)
+        Wp = bs_ref.unpack(v1, i1, bank)
+        v2, i2 = bs_ref.prune_pack(Wp, bank, k)
+        v3, i3 = bs_ref.prune_pack(W, bank, k)
+        assert np.array_equal(i2, i3) and v2.tobytes() == v3.tobytes()
+
+
+def test_counts_and_sparsity():
+    for name, wl in workloads.WORKLOADS.items():
+        assert wl.K % wl.bank == 0
+        assert wl.nnz == wl.M * (wl.K // wl.bank) * wl.k
+    assert workloads.WORKLOADS["lstm1500"].sparsity == pytest.approx(0.9)
+    assert workloads.WORKLOADS["fc6_b1"].sparsity == 1 - 6 / 64
+    assert workloads.WORKLOADS["lstm1500"].spmv_bytes() == 9036000
+    assert workloads.WORKLOADS["fc6_b1"].spmv_bytes() == 29018112
+    assert workloads.WORKLOADS["lstm1500_n128"].spmv_bytes() == 13608000
+
+
+# ------------------------------------------------------ statistical sanity
+
+def test_gaussian_cut_and_zero_mean_difference():
+    """Sec. 3.3: Gaussian weights; keeping the top 10 % by magnitude cuts near
+    the two-sided 90 % quantile (1.645 sigma), and Theorem 1 says the output
+    difference between pruned and dense layer has mean zero."""
+    sigma = 0.05
+    W = workloads.draw_weights(400, 3000, sigma, "f32", 21)
+    x = workloads.draw_activations(3000, 1, 21)
+    vals, idx = bs_ref.prune_pack(W, 100, 10)
+    cut = np.abs(vals).min(axis=2).mean()
+    assert abs(cut / sigma - 1.645) < 0.12   # order statistic bias is small at B=100
+    Wp = bs_ref.unpack(vals, idx, 100)
+    z = (Wp.astype(np.float64) - W.astype(np.float64)) @ x.astype(np.float64)
+    se = z.std(ddof=1) / np.sqrt(z.size)
+    assert abs(z.mean()) < 4 * se
+
+
+# ------------------------------------------------------ threads, errors
+
+def test_row_split_threads_give_identical_results():
+    W = rand_w(37, 300, 22)
+    X = workloads.draw_activations(300, 3, 22)
+    vals, idx = bs_ref.prune_pack(W, 100, 10)
+    Y1 = bs_ref.spmm(vals, idx, 100, X, threads=1)
+    Y5 = bs_ref.spmm(vals, idx, 100, X, threads=5)
+    assert Y1.tobytes() == Y5.tobytes()
+
+
+def test_errors():
+    W = rand_w(2, 64, 23)
+    with pytest.raises(bs_ref.OracleError):
+        bs_ref.prune_pack(W, 48, 4)          # K % bank != 0
+    with pytest.raises(bs_ref.OracleError):
+        bs_ref.prune_pack(W, 32, 33)         # k > bank
+    Wn = W.copy()
+    Wn[1, 5] = np.nan
+    with pytest.raises(bs_ref.OracleError) as e:
+        bs_ref.prune_pack(Wn, 32, 4)
+    assert e.value.status == bs_ref.ERR_NONFINITE
+
+
+def test_rel_l2():
+    b = np.array([3.0, 4.0], dtype=np.float32)
+    a = np.array([3.0, 4.5], dtype=np.float32)
+    assert bs_ref.rel_l2(a, b) == pytest.approx(0.1)
+    assert bs_ref.rel_l2(b, b) == 0.0
