@@ -96,10 +96,15 @@ int bs_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t 
  *   rows_per_wg    rows handled by one workgroup; lanes_per_row*rows_per_wg must
  *                  be a multiple of 64 and at most 1024; 0 = choose
  * Invalid combinations return BS_ERR_UNSUPPORTED.
+ *   start_event, stop_event  optional hipEvent_t handles (NULL = none) that
+ *                  receive the kernel's own begin and end time stamps on the
+ *                  GPU, so one launch can be timed without the gaps between
+ *                  launches (hipEventElapsedTime after synchronising).
  */
 int bs_spmv_ex(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K,
                int bank, int k, const float* x, float* y,
-               int lanes_per_row, int rows_per_wg, void* stream);
+               int lanes_per_row, int rows_per_wg,
+               void* start_event, void* stop_event, void* stream);
 
 /* ---- Y = W_sparse . X  (Sec. 3.4 / Sec. 4.1, batch size > 1; im2col conv) - */
 

@@ -1,0 +1,237 @@
+"""Python names for the C-ABI calls of ``libbs.so`` (see ``include/bs.h``).
+
+Argument marshalling only: each function checks tensor device / dtype /
+contiguity, passes raw device pointers and torch's current HIP stream to the
+library, and raises :class:`BsError` on a non-zero status.  There is no Python
+or CPU implementation behind these names; if the library is missing the first
+call fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libbs.so")
+
+BS_F32, BS_F16 = 0, 1
+
+EXPORTS = (
+    "bs_nnz", "bs_vals_bytes", "bs_idx_bytes", "bs_status_str", "bs_prune_pack", "bs_spmv",
+    "bs_spmv_ex", "bs_spmm_workspace_bytes", "bs_spmm", "bs_dense_gemv", "bs_dense_gemm",
+)
+
+
+class BsError(RuntimeError):
+    def __init__(self, status: int, call: str):
+        self.status = status
+        super().__init__(f"{call}: {bs_status_str(status)} (status {status})")
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load ``libbs.so`` (built by ``python -m paper_1811_00206_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_1811_00206_amd.build`; "
+            "there is no fallback implementation")
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+    lib.bs_nnz.argtypes = [i64, i64, i32, i32]
+    lib.bs_nnz.restype = sz
+    lib.bs_vals_bytes.argtypes = [i64, i64, i32, i32, i32]
+    lib.bs_vals_bytes.restype = sz
+    lib.bs_idx_bytes.argtypes = [i64, i64, i32, i32]
+    lib.bs_idx_bytes.restype = sz
+    lib.bs_status_str.argtypes = [i32]
+    lib.bs_status_str.restype = ctypes.c_char_p
+    lib.bs_prune_pack.argtypes = [vp, i32, i64, i64, i32, i32, vp, vp, vp]
+    lib.bs_spmv.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, vp, vp]
+    lib.bs_spmv_ex.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, vp, i32, i32, vp, vp, vp]
+    lib.bs_spmm_workspace_bytes.argtypes = [i32, i64, i64, i32, i32, i64]
+    lib.bs_spmm_workspace_bytes.restype = sz
+    lib.bs_spmm.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, i64, vp, i64, vp, sz, vp]
+    lib.bs_dense_gemv.argtypes = [vp, i32, i64, i64, vp, vp, vp]
+    lib.bs_dense_gemm.argtypes = [vp, i32, i64, i64, vp, i64, i64, vp, i64, vp]
+    for name in ("bs_prune_pack", "bs_spmv", "bs_spmv_ex", "bs_spmm", "bs_dense_gemv",
+                 "bs_dense_gemm"):
+        getattr(lib, name).restype = i32
+    _lib = lib
+    return lib
+
+
+# ------------------------------------------------------------------ helpers
+
+def _dtype_code(t: torch.Tensor, what: str) -> int:
+    if t.dtype == torch.float32:
+        return BS_F32
+    if t.dtype == torch.float16:
+        return BS_F16
+    raise TypeError(f"{what} must be float32 or float16, got {t.dtype}")
+
+
+def _dev(t: torch.Tensor, what: str, dtype=None) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{what} must be a tensor on the GPU")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{what} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+    return t
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t) -> ctypes.c_void_p:
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _check(status: int, call: str):
+    if status != 0:
+        raise BsError(status, call)
+
+
+# ------------------------------------------------------------ host-only calls
+
+def bs_nnz(M: int, K: int, bank: int, k: int) -> int:
+    return load_library().bs_nnz(M, K, bank, k)
+
+
+def bs_vals_bytes(M: int, K: int, bank: int, k: int, dtype: int) -> int:
+    return load_library().bs_vals_bytes(M, K, bank, k, dtype)
+
+
+def bs_idx_bytes(M: int, K: int, bank: int, k: int) -> int:
+    return load_library().bs_idx_bytes(M, K, bank, k)
+
+
+def bs_status_str(status: int) -> str:
+    return load_library().bs_status_str(status).decode()
+
+
+def bs_spmm_workspace_bytes(dtype: int, M: int, K: int, bank: int, k: int, N: int) -> int:
+    return load_library().bs_spmm_workspace_bytes(dtype, M, K, bank, k, N)
+
+
+# --------------------------------------------------------------- GPU calls
+
+def bs_prune_pack(W: torch.Tensor, bank: int, k: int):
+    """W [M, K] on the GPU (fp32/fp16) -> (vals [M, K/bank, k], idx uint8 same shape)."""
+    _dev(W, "W")
+    code = _dtype_code(W, "W")
+    if W.dim() != 2:
+        raise ValueError("W must be 2-D")
+    M, K = W.shape
+    if bank < 1 or K % bank or k < 1 or k > bank:
+        raise BsError(2, "bs_prune_pack")
+    nb = K // bank
+    vals = torch.empty((M, nb, k), dtype=W.dtype, device=W.device)
+    idx = torch.empty((M, nb, k), dtype=torch.uint8, device=W.device)
+    _check(load_library().bs_prune_pack(_ptr(W), code, M, K, bank, k, _ptr(vals), _ptr(idx),
+                                        _stream()), "bs_prune_pack")
+    return vals, idx
+
+
+def _packed(vals, idx, bank):
+    _dev(vals, "vals")
+    _dev(idx, "idx", torch.uint8)
+    if vals.dim() != 3 or idx.shape != vals.shape:
+        raise ValueError("vals and idx must both be [M, K/bank, k]")
+    M, nb, k = vals.shape
+    return _dtype_code(vals, "vals"), M, nb * bank, k
+
+
+def bs_spmv(vals, idx, bank: int, x, out=None, lanes_per_row: int = 0, rows_per_wg: int = 0,
+            start_event: int = 0, stop_event: int = 0):
+    """y [M] = W_sparse . x, x [K] fp32 on the GPU.  start_event / stop_event are
+    optional raw hipEvent_t handles that receive the kernel's own time stamps."""
+    code, M, K, k = _packed(vals, idx, bank)
+    _dev(x, "x", torch.float32)
+    if x.numel() != K:
+        raise ValueError(f"x must have {K} elements")
+    y = torch.empty(M, dtype=torch.float32, device=vals.device) if out is None else _dev(
+        out, "out", torch.float32)
+    if y.numel() != M:
+        raise ValueError(f"out must have {M} elements")
+    lib = load_library()
+    if lanes_per_row or rows_per_wg or start_event or stop_event:
+        st = lib.bs_spmv_ex(_ptr(vals), _ptr(idx), code, M, K, bank, k, _ptr(x), _ptr(y),
+                            lanes_per_row, rows_per_wg, ctypes.c_void_p(start_event),
+                            ctypes.c_void_p(stop_event), _stream())
+    else:
+        st = lib.bs_spmv(_ptr(vals), _ptr(idx), code, M, K, bank, k, _ptr(x), _ptr(y), _stream())
+    _check(st, "bs_spmv")
+    return y
+
+
+def bs_spmv_ex(vals, idx, bank, x, lanes_per_row, rows_per_wg, out=None, start_event=0,
+               stop_event=0):
+    return bs_spmv(vals, idx, bank, x, out=out, lanes_per_row=lanes_per_row,
+                   rows_per_wg=rows_per_wg, start_event=start_event, stop_event=stop_event)
+
+
+def bs_spmm(vals, idx, bank: int, X, out=None, workspace=None):
+    """Y [M, N] = W_sparse . X, X [K, N] fp32 row-major on the GPU.  `workspace`
+    is an optional uint8 tensor of at least bs_spmm_workspace_bytes(...) bytes;
+    without it one is taken from torch's allocator for this call."""
+    code, M, K, k = _packed(vals, idx, bank)
+    _dev(X, "X", torch.float32)
+    if X.dim() != 2 or X.shape[0] != K:
+        raise ValueError(f"X must be [{K}, N]")
+    N = X.shape[1]
+    Y = torch.empty((M, N), dtype=torch.float32, device=vals.device) if out is None else _dev(
+        out, "out", torch.float32)
+    if tuple(Y.shape) != (M, N):
+        raise ValueError(f"out must be [{M}, {N}]")
+    lib = load_library()
+    need = lib.bs_spmm_workspace_bytes(code, M, K, bank, k, N)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=vals.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.bs_spmm(_ptr(vals), _ptr(idx), code, M, K, bank, k, _ptr(X), N, N, _ptr(Y), N,
+                       _ptr(workspace), ws_bytes, _stream()), "bs_spmm")
+    return Y
+
+
+def bs_dense_gemv(W, x, out=None):
+    """y = W . x with the hand-written dense baseline kernel."""
+    _dev(W, "W")
+    code = _dtype_code(W, "W")
+    M, K = W.shape
+    _dev(x, "x", torch.float32)
+    if x.numel() != K:
+        raise ValueError(f"x must have {K} elements")
+    y = torch.empty(M, dtype=torch.float32, device=W.device) if out is None else _dev(
+        out, "out", torch.float32)
+    _check(load_library().bs_dense_gemv(_ptr(W), code, M, K, _ptr(x), _ptr(y), _stream()),
+           "bs_dense_gemv")
+    return y
+
+
+def bs_dense_gemm(W, X, out=None):
+    """Y = W . X with the hand-written dense baseline kernel."""
+    _dev(W, "W")
+    code = _dtype_code(W, "W")
+    M, K = W.shape
+    _dev(X, "X", torch.float32)
+    if X.dim() != 2 or X.shape[0] != K:
+        raise ValueError(f"X must be [{K}, N]")
+    N = X.shape[1]
+    Y = torch.empty((M, N), dtype=torch.float32, device=W.device) if out is None else _dev(
+        out, "out", torch.float32)
+    _check(load_library().bs_dense_gemm(_ptr(W), code, M, K, _ptr(X), N, N, _ptr(Y), N, _stream()),
+           "bs_dense_gemm")
+    return Y

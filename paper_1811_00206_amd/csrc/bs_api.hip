@@ -1,0 +1,123 @@
+// C-ABI entry points of libbs.so: argument validation on the host, then the
+// launchers.  Nothing here allocates, synchronises or keeps state.
+#include "bs_internal.h"
+
+namespace {
+
+bool shape_ok(int64_t M, int64_t K, int bank, int k) {
+    return M >= 1 && K >= 1 && bank >= 1 && k >= 1 && k <= bank && K % bank == 0;
+}
+
+// limits stated in bs.h
+bool size_ok(int64_t M, int64_t K, int bank) {
+    return bank <= 256 && K <= ((int64_t)1 << 24) && M <= ((int64_t)1 << 40) / K;
+}
+
+bool dtype_ok(int dtype) { return dtype == BS_F32 || dtype == BS_F16; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_packed(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                 int k) {
+    if (!vals || !idx) return BS_ERR_NULL;
+    if (!shape_ok(M, K, bank, k)) return BS_ERR_SHAPE;
+    if (!dtype_ok(dtype) || !size_ok(M, K, bank)) return BS_ERR_UNSUPPORTED;
+    if (!aligned16(vals) || !aligned16(idx)) return BS_ERR_ALIGN;
+    return BS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t bs_nnz(int64_t M, int64_t K, int bank, int k) {
+    if (!shape_ok(M, K, bank, k) || !size_ok(M, K, bank)) return 0;
+    return (size_t)M * (size_t)(K / bank) * (size_t)k;
+}
+
+size_t bs_vals_bytes(int64_t M, int64_t K, int bank, int k, int dtype) {
+    if (!dtype_ok(dtype)) return 0;
+    return bs_nnz(M, K, bank, k) * (dtype == BS_F16 ? 2 : 4);
+}
+
+size_t bs_idx_bytes(int64_t M, int64_t K, int bank, int k) { return bs_nnz(M, K, bank, k); }
+
+const char* bs_status_str(int status) {
+    switch (status) {
+        case BS_OK: return "ok";
+        case BS_ERR_NULL: return "null pointer";
+        case BS_ERR_SHAPE: return "invalid shape";
+        case BS_ERR_UNSUPPORTED: return "unsupported size, dtype or launch shape";
+        case BS_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case BS_ERR_HIP: return "HIP runtime error";
+        case BS_ERR_WORKSPACE: return "workspace missing or too small";
+    }
+    return "unknown status";
+}
+
+int bs_prune_pack(const void* W, int dtype, int64_t M, int64_t K, int bank, int k, void* vals,
+                  uint8_t* idx, void* stream) {
+    if (!W) return BS_ERR_NULL;
+    int st = check_packed(vals, idx, dtype, M, K, bank, k);
+    if (st) return st;
+    if (!aligned16(W)) return BS_ERR_ALIGN;
+    return bs::launch_prune_pack(W, dtype, M, K, bank, k, vals, idx,
+                                 static_cast<hipStream_t>(stream));
+}
+
+int bs_spmv_ex(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
+               int k, const float* x, float* y, int lanes_per_row, int rows_per_wg,
+               void* start_event, void* stop_event, void* stream) {
+    if (!x || !y) return BS_ERR_NULL;
+    int st = check_packed(vals, idx, dtype, M, K, bank, k);
+    if (st) return st;
+    if (!aligned16(x) || !aligned16(y)) return BS_ERR_ALIGN;
+    if (lanes_per_row < 0 || rows_per_wg < 0) return BS_ERR_UNSUPPORTED;
+    return bs::launch_spmv(vals, idx, dtype, M, K, bank, k, x, y, lanes_per_row, rows_per_wg,
+                           static_cast<hipEvent_t>(start_event),
+                           static_cast<hipEvent_t>(stop_event),
+                           static_cast<hipStream_t>(stream));
+}
+
+int bs_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
+            int k, const float* x, float* y, void* stream) {
+    return bs_spmv_ex(vals, idx, dtype, M, K, bank, k, x, y, 0, 0, nullptr, nullptr, stream);
+}
+
+size_t bs_spmm_workspace_bytes(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N) {
+    if (!shape_ok(M, K, bank, k) || !dtype_ok(dtype) || !size_ok(M, K, bank) || N < 1) return 0;
+    return bs::spmm_workspace_bytes(dtype, M, K, bank, k, N);
+}
+
+int bs_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
+            int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
+            void* workspace, size_t workspace_bytes, void* stream) {
+    if (!X || !Y) return BS_ERR_NULL;
+    int st = check_packed(vals, idx, dtype, M, K, bank, k);
+    if (st) return st;
+    if (N < 1 || ldx < N || ldy < N) return BS_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(Y)) return BS_ERR_ALIGN;
+    return bs::launch_spmm(vals, idx, dtype, M, K, bank, k, X, N, ldx, Y, ldy, workspace,
+                           workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+int bs_dense_gemv(const void* W, int dtype, int64_t M, int64_t K, const float* x, float* y,
+                  void* stream) {
+    if (!W || !x || !y) return BS_ERR_NULL;
+    if (M < 1 || K < 1) return BS_ERR_SHAPE;
+    if (!dtype_ok(dtype)) return BS_ERR_UNSUPPORTED;
+    if (!aligned16(W) || !aligned16(x) || !aligned16(y)) return BS_ERR_ALIGN;
+    return bs::launch_dense_gemv(W, dtype, M, K, x, y, static_cast<hipStream_t>(stream));
+}
+
+int bs_dense_gemm(const void* W, int dtype, int64_t M, int64_t K, const float* X, int64_t N,
+                  int64_t ldx, float* Y, int64_t ldy, void* stream) {
+    if (!W || !X || !Y) return BS_ERR_NULL;
+    if (M < 1 || K < 1 || N < 1 || ldx < N || ldy < N) return BS_ERR_SHAPE;
+    if (!dtype_ok(dtype)) return BS_ERR_UNSUPPORTED;
+    if (!aligned16(W) || !aligned16(X) || !aligned16(Y)) return BS_ERR_ALIGN;
+    return bs::launch_dense_gemm(W, dtype, M, K, X, N, ldx, Y, ldy,
+                                 static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,187 @@
+// Dense baselines: y = W.x and Y = W.X over all K columns (arXiv 1811.00206,
+// Sec. 4: every table and Fig. 4 compare the sparse multiply with a dense one;
+// eq. (5) builds its ideal time from the dense time).  These are plain
+// hand-written kernels on the same GPU, so the speedup column has an honest
+// denominator; they are not part of the sparse path.
+#include "bs_internal.h"
+
+namespace bs {
+namespace {
+
+template <typename VT> struct Vec16;   // 16 bytes of VT
+template <> struct Vec16<float> { static constexpr int n = 4; };
+template <> struct Vec16<__half> { static constexpr int n = 8; };
+
+template <typename VT>
+__device__ __forceinline__ float to_f32(VT v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<__half>(__half v) { return __half2float(v); }
+
+// ---- GEMV: one wavefront per R rows, lanes stride the row in 16-byte pieces --
+template <typename VT, int R, bool VEC>
+__global__ __launch_bounds__(256) void dense_gemv_kernel(const VT* __restrict__ W,
+                                                         const float* __restrict__ x,
+                                                         float* __restrict__ y, int M, int K) {
+    constexpr int N16 = Vec16<VT>::n;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+    const int r0 = wave * R;
+    if (r0 >= M) return;   // whole wavefront leaves together
+    float acc[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[r] = 0.f;
+
+    if constexpr (VEC) {
+        const int steps = K / N16;
+        for (int c = lane; c < steps; c += kWave) {
+            float xv[N16];
+#pragma unroll
+            for (int q = 0; q < N16 / 4; ++q) {
+                float4 t = reinterpret_cast<const float4*>(x)[c * (N16 / 4) + q];
+                xv[q * 4 + 0] = t.x; xv[q * 4 + 1] = t.y; xv[q * 4 + 2] = t.z; xv[q * 4 + 3] = t.w;
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                int row = r0 + r < M ? r0 + r : M - 1;
+                uint4 raw = reinterpret_cast<const uint4*>(W + (size_t)row * K)[c];
+                VT w[N16];
+                __builtin_memcpy(w, &raw, 16);
+#pragma unroll
+                for (int i = 0; i < N16; ++i) acc[r] = fmaf(to_f32<VT>(w[i]), xv[i], acc[r]);
+            }
+        }
+    } else {
+        for (int c = lane; c < K; c += kWave) {
+            float xv = x[c];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                int row = r0 + r < M ? r0 + r : M - 1;
+                acc[r] = fmaf(to_f32<VT>(W[(size_t)row * K + c]), xv, acc[r]);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        float s = group_sum<64>(acc[r]);
+        if (lane == 0 && r0 + r < M) y[r0 + r] = s;
+    }
+}
+
+// ---- GEMM: 64 x BN output tile per workgroup, K in steps of 32 through LDS ---
+constexpr int BM = 64, BK = 32;
+
+template <typename VT, int BN>
+__global__ __launch_bounds__(256) void dense_gemm_kernel(const VT* __restrict__ W,
+                                                         const float* __restrict__ X,
+                                                         float* __restrict__ Y, int M, int K,
+                                                         int N, int64_t ldx, int64_t ldy) {
+    constexpr int TN = BN / 16;            // columns per thread
+    __shared__ float As[BK][BM + 4];       // W tile, k-major
+    __shared__ float Bs[BK][BN];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;   // 16 x 16 threads, 4 x TN outputs each
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+
+    float acc[4][TN];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = 0.f;
+
+    for (int k0 = 0; k0 < K; k0 += BK) {
+        // W tile: 64 rows x 32 k; thread loads 8 consecutive k of one row
+        {
+            int r = tid >> 2, kq = (tid & 3) * 8;
+            int row = m0 + r;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                int kk = k0 + kq + i;
+                float v = 0.f;
+                if (row < M && kk < K) v = to_f32<VT>(W[(size_t)row * K + kk]);
+                As[kq + i][r] = v;
+            }
+        }
+        // X tile: 32 k x BN columns
+        for (int e = tid; e < BK * BN; e += 256) {
+            int kk = e / BN, n = e % BN;
+            float v = 0.f;
+            if (k0 + kk < K && n0 + n < N) v = X[(size_t)(k0 + kk) * ldx + n0 + n];
+            Bs[kk][n] = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK; ++kk) {
+            float a[4], b[TN];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = Bs[kk][tx * TN + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int row = m0 + ty * 4 + i;
+        if (row >= M) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            int n = n0 + tx * TN + j;
+            if (n < N) Y[(size_t)row * ldy + n] = acc[i][j];
+        }
+    }
+}
+
+template <typename VT>
+int gemv_t(const void* W, int64_t M, int64_t K, const float* x, float* y, hipStream_t st) {
+    constexpr int R = 2;
+    const int threads = 256;
+    const int64_t waves = (M + R - 1) / R;
+    const int64_t grid = (waves + threads / kWave - 1) / (threads / kWave);
+    const VT* w = static_cast<const VT*>(W);
+    if (K % Vec16<VT>::n == 0)
+        hipLaunchKernelGGL((dense_gemv_kernel<VT, R, true>), dim3((unsigned)grid), dim3(threads), 0, st, w, x, y, (int)M, (int)K);
+    else
+        hipLaunchKernelGGL((dense_gemv_kernel<VT, R, false>), dim3((unsigned)grid), dim3(threads), 0, st, w, x, y, (int)M, (int)K);
+    return hip_status(hipGetLastError());
+}
+
+template <typename VT>
+int gemm_t(const void* W, int64_t M, int64_t K, const float* X, int64_t N, int64_t ldx, float* Y,
+           int64_t ldy, hipStream_t st) {
+    const VT* w = static_cast<const VT*>(W);
+    const unsigned gm = (unsigned)((M + BM - 1) / BM);
+    if (N <= 16) {
+        dim3 g(gm, (unsigned)((N + 15) / 16));
+        hipLaunchKernelGGL((dense_gemm_kernel<VT, 16>), g, dim3(256), 0, st, w, X, Y, (int)M, (int)K, (int)N, ldx, ldy);
+    } else if (N <= 32) {
+        dim3 g(gm, 1);
+        hipLaunchKernelGGL((dense_gemm_kernel<VT, 32>), g, dim3(256), 0, st, w, X, Y, (int)M, (int)K, (int)N, ldx, ldy);
+    } else {
+        dim3 g(gm, (unsigned)((N + 63) / 64));
+        hipLaunchKernelGGL((dense_gemm_kernel<VT, 64>), g, dim3(256), 0, st, w, X, Y, (int)M, (int)K, (int)N, ldx, ldy);
+    }
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace
+
+int launch_dense_gemv(const void* W, int dtype, int64_t M, int64_t K, const float* x, float* y,
+                      hipStream_t st) {
+    if (M > INT32_MAX / 2 || K > INT32_MAX / 2) return BS_ERR_UNSUPPORTED;
+    if (dtype == BS_F16) return gemv_t<__half>(W, M, K, x, y, st);
+    return gemv_t<float>(W, M, K, x, y, st);
+}
+
+int launch_dense_gemm(const void* W, int dtype, int64_t M, int64_t K, const float* X, int64_t N,
+                      int64_t ldx, float* Y, int64_t ldy, hipStream_t st) {
+    if (M > INT32_MAX / 2 || K > INT32_MAX / 2 || N > INT32_MAX / 2) return BS_ERR_UNSUPPORTED;
+    if ((N + 63) / 64 > 65535) return BS_ERR_UNSUPPORTED;
+    if (dtype == BS_F16) return gemm_t<__half>(W, M, K, X, N, ldx, Y, ldy, st);
+    return gemm_t<float>(W, M, K, X, N, ldx, Y, ldy, st);
+}
+
+}  // namespace bs

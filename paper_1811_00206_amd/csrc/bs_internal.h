@@ -1,0 +1,124 @@
+// Internal declarations shared by the HIP translation units of libbs.so.
+// gfx950 (CDNA4) only: 64-lane wavefronts, 160 KB LDS per compute unit.
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_ext.h>
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/bs.h"
+
+namespace bs {
+
+constexpr int kWave = 64;
+constexpr int kMaxLdsBytes = 160 * 1024;   // LDS of one gfx950 compute unit
+
+// Launchers (host).  Arguments are already validated by the C-ABI layer.
+int launch_prune_pack(const void* W, int dtype, int64_t M, int64_t K, int bank, int k,
+                      void* vals, uint8_t* idx, hipStream_t st);
+int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                int k, const float* x, float* y, int lanes_per_row, int rows_per_wg,
+                hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st);
+size_t spmm_workspace_bytes(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N);
+int launch_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
+                void* workspace, size_t workspace_bytes, hipStream_t st);
+int launch_dense_gemv(const void* W, int dtype, int64_t M, int64_t K, const float* x, float* y,
+                      hipStream_t st);
+int launch_dense_gemm(const void* W, int dtype, int64_t M, int64_t K, const float* X, int64_t N,
+                      int64_t ldx, float* Y, int64_t ldy, hipStream_t st);
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? BS_OK : BS_ERR_HIP; }
+
+// Multiplier m with floor(e / d) == __umulhi(e, m) for every e with e * d < 2^32
+// (d >= 2).  d == 1 is handled by the caller (quotient = e).
+inline uint32_t magic_u32(uint32_t d) {
+    return d < 2 ? 0u : (uint32_t)(((uint64_t)1 << 32) / d + 1);
+}
+
+#ifdef __HIPCC__
+
+__device__ __forceinline__ uint32_t div_magic(uint32_t e, uint32_t d, uint32_t magic) {
+    return d == 1 ? e : __umulhi(e, magic);
+}
+
+// ---- cross-lane sums over aligned groups of W lanes (W = 1,2,4,...,64) -----
+// Data-parallel-primitive moves inside a 16-lane row; the two widest steps go
+// through the LDS crossbar (no LDS memory is touched).  After the call every
+// lane of the group holds the group's sum; the order of additions is fixed.
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    int i = __builtin_bit_cast(int, v);
+    int r = __builtin_amdgcn_update_dpp(0, i, CTRL, 0xf, 0xf, true);
+    return __builtin_bit_cast(float, r);
+}
+
+template <int W>
+__device__ __forceinline__ float group_sum(float v) {
+    static_assert(W >= 1 && W <= 64 && (W & (W - 1)) == 0, "group width");
+    if constexpr (W >= 2) v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+    if constexpr (W >= 4) v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+    if constexpr (W >= 8) v += dpp_move<0x141>(v);   // row_half_mirror
+    if constexpr (W >= 16) v += dpp_move<0x140>(v);  // row_mirror
+    if constexpr (W >= 32) v += __shfl_xor(v, 16, 64);
+    if constexpr (W >= 64) v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
+// number of set bits of `mask` below the calling lane
+__device__ __forceinline__ int lanes_below(uint64_t mask) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+}
+
+// ---- raw chunks of the packed stream: CH values and CH offset bytes, each
+//      fetched with one load instruction ------------------------------------
+
+template <int BYTES>
+struct RawBytes;
+template <> struct RawBytes<1> { using type = uint8_t; };
+template <> struct RawBytes<2> { using type = uint16_t; };
+template <> struct RawBytes<4> { using type = uint32_t; };
+template <> struct RawBytes<8> { using type = uint2; };
+template <> struct RawBytes<16> { using type = uint4; };
+
+template <typename T>
+__device__ __forceinline__ uint32_t word_of(const T& v, int w);
+template <> __device__ __forceinline__ uint32_t word_of<uint8_t>(const uint8_t& v, int) { return v; }
+template <> __device__ __forceinline__ uint32_t word_of<uint16_t>(const uint16_t& v, int) { return v; }
+template <> __device__ __forceinline__ uint32_t word_of<uint32_t>(const uint32_t& v, int) { return v; }
+template <> __device__ __forceinline__ uint32_t word_of<uint2>(const uint2& v, int w) { return w ? v.y : v.x; }
+template <> __device__ __forceinline__ uint32_t word_of<uint4>(const uint4& v, int w) {
+    return w == 0 ? v.x : w == 1 ? v.y : w == 2 ? v.z : v.w;
+}
+
+// i-th value of a raw chunk as fp32 (binary16 widens exactly)
+template <typename VT, typename RAW>
+__device__ __forceinline__ float value_at(const RAW& raw, int i) {
+    if constexpr (sizeof(VT) == 4) {
+        return __builtin_bit_cast(float, word_of(raw, i));
+    } else {
+        uint32_t w = word_of(raw, i >> 1);
+        uint16_t h = (i & 1) ? (uint16_t)(w >> 16) : (uint16_t)(w & 0xffffu);
+        return __half2float(__builtin_bit_cast(__half, h));
+    }
+}
+
+template <typename RAW>
+__device__ __forceinline__ uint32_t offset_at(const RAW& raw, int i) {
+    return (word_of(raw, i >> 2) >> ((i & 3) * 8)) & 0xffu;
+}
+
+template <typename T>
+__device__ __forceinline__ T zero_raw() {
+    T z;
+    __builtin_memset(&z, 0, sizeof(T));
+    return z;
+}
+
+#endif  // __HIPCC__
+
+}  // namespace bs

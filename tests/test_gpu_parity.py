@@ -1,0 +1,262 @@
+"""GPU parity: the HIP path, called through the C-ABI binding, against the CPU
+oracle on the same seeded inputs.  vals/idx must match bit for bit; products
+must stay within 1e-5 relative L2 (fp32 storage) or 1e-2 (fp16 storage)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import bs_ref
+from paper_1811_00206_amd import binding as bs
+from paper_1811_00206_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "f16": 1e-2}
+DEV = "cuda:0"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def check_pack(W, bank, k):
+    v_ref, i_ref = bs_ref.prune_pack(W, bank, k)
+    v, i = bs.bs_prune_pack(dev(W), bank, k)
+    v, i = host(v), host(i)
+    assert i.shape == i_ref.shape and v.dtype == v_ref.dtype
+    assert i.tobytes() == i_ref.tobytes(), "idx differs"
+    assert v.tobytes() == v_ref.tobytes(), "vals differ"
+    return v_ref, i_ref
+
+
+SMALL_SHAPES = [(7, 64, 16, 4), (5, 300, 100, 10), (3, 256, 64, 1), (4, 96, 32, 31),
+                (2, 512, 256, 13), (9, 30, 3, 2), (1, 128, 128, 5), (6, 40, 1, 1),
+                (33, 520, 130, 7), (17, 768, 192, 192), (1, 4, 4, 4), (257, 200, 100, 99),
+                (1000, 64, 64, 64), (3, 2048, 256, 255)]
+
+
+# ------------------------------------------------------------ prune + pack
+
+@pytest.mark.parametrize("M,K,bank,k", SMALL_SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_prune_pack_small(M, K, bank, k, dtype):
+    say("prune_pack small", M, K, bank, k, dtype)
+    W = workloads.draw_weights(M, K, 1.0, dtype, 31)
+    check_pack(W, bank, k)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("levels", [1, 2, 3, 5])
+def test_prune_pack_ties(dtype, levels):
+    say("prune_pack ties", dtype, levels)
+    W = workloads.tie_heavy_weights(64, 1024, levels, dtype, 32)
+    for bank, k in [(64, 16), (32, 5), (256, 100), (4, 2), (128, 127), (1, 1), (64, 64)]:
+        check_pack(W, bank, k)
+
+
+def test_prune_pack_special_values():
+    # signed zeros, subnormals, largest finite; all-zero banks
+    W = np.zeros((4, 128), dtype=np.float32)
+    W[0, ::3] = -0.0
+    W[1, :] = np.float32(1e-45)
+    W[1, 5] = -np.float32(1e-45) * 3
+    W[2, :] = np.finfo(np.float32).max
+    W[2, ::2] *= -1
+    W[3, :] = np.linspace(-1, 1, 128, dtype=np.float32)
+    for bank, k in [(128, 7), (64, 32), (32, 1)]:
+        check_pack(W, bank, k)
+    Wh = W.astype(np.float16)
+    Wh[2, :] = np.float16(65504)
+    Wh[1, :] = np.array([0x0001], dtype=np.uint16).view(np.float16)[0]
+    for bank, k in [(128, 7), (64, 32), (32, 1)]:
+        check_pack(Wh, bank, k)
+
+
+FULL = ["tiny", "lstm1500", "sweep_k32", "sweep_k16", "sweep_k8", "sweep_k4", "sweep_k2",
+        "fc6_b1"]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_pack_and_spmv(name):
+    """The five configurations at full size: pack bit-exact, product in tolerance,
+    in the launch shape the bench times (the default one)."""
+    say("full", name)
+    wl, W, x = workloads.make(name)
+    v_ref, i_ref = check_pack(W, wl.bank, wl.k)
+    y_ref = bs_ref.spmv(v_ref, i_ref, wl.bank, x, threads=bs_ref.host_threads())
+    vals, idx = dev(v_ref), dev(i_ref)
+    y = bs.bs_spmv(vals, idx, wl.bank, dev(x))
+    err = bs_ref.rel_l2(host(y), y_ref)
+    say("  spmv relL2", err)
+    assert err <= TOL[wl.dtype]
+    # bit-reproducible from call to call
+    y2 = bs.bs_spmv(vals, idx, wl.bank, dev(x))
+    assert host(y).tobytes() == host(y2).tobytes()
+
+
+# ------------------------------------------------------------------- SpMV
+
+@pytest.mark.parametrize("M,K,bank,k", SMALL_SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_spmv_small(M, K, bank, k, dtype):
+    say("spmv small", M, K, bank, k, dtype)
+    W = workloads.draw_weights(M, K, 0.05, dtype, 33)
+    x = workloads.draw_activations(K, 1, 33)
+    v, i = bs_ref.prune_pack(W, bank, k)
+    y_ref = bs_ref.spmv(v, i, bank, x)
+    y = host(bs.bs_spmv(dev(v), dev(i), bank, dev(x)))
+    assert bs_ref.rel_l2(y, y_ref) <= TOL[dtype]
+    # element by element as well (a single wrong row hides in an L2 norm)
+    scale = np.abs(y_ref).max() + 1e-30
+    assert np.abs(y - y_ref).max() <= (1e-5 if dtype == "f32" else 1e-2) * scale
+
+
+@pytest.mark.parametrize("lanes", [1, 2, 4, 8, 16, 32, 64])
+def test_spmv_every_launch_shape(lanes):
+    say("spmv launch shapes", lanes)
+    for name, rows in [("tiny", None), ("lstm1500", 1000)]:
+        wl, W, x = workloads.make(name, rows=rows)
+        v, i = bs_ref.prune_pack(W, wl.bank, wl.k)
+        y_ref = bs_ref.spmv(v, i, wl.bank, x)
+        vd, idd, xd = dev(v), dev(i), dev(x)
+        for threads in (64, 256, 1024):
+            y = host(bs.bs_spmv_ex(vd, idd, wl.bank, xd, lanes, threads // lanes))
+            assert bs_ref.rel_l2(y, y_ref) <= 1e-5, (name, lanes, threads)
+
+
+def test_spmv_largest_x_that_fits_lds_and_beyond():
+    K = 40960                      # 160 KB of fp32: the whole LDS of a compute unit
+    say("spmv K", K)
+    W = workloads.draw_weights(48, K, 1.0, "f32", 34)
+    x = workloads.draw_activations(K, 1, 34)
+    v, i = bs_ref.prune_pack(W, 256, 3)
+    y = host(bs.bs_spmv(dev(v), dev(i), 256, dev(x)))
+    assert bs_ref.rel_l2(y, bs_ref.spmv(v, i, 256, x)) <= 1e-5
+    K2 = K + 256
+    v2 = torch.zeros((2, K2 // 256, 3), dtype=torch.float32, device=DEV)
+    i2 = torch.zeros((2, K2 // 256, 3), dtype=torch.uint8, device=DEV)
+    with pytest.raises(bs.BsError) as e:
+        bs.bs_spmv(v2, i2, 256, torch.zeros(K2, device=DEV))
+    assert e.value.status == 3
+
+
+# ------------------------------------------------------------------- SpMM
+
+def check_spmm(W, bank, k, X, tol):
+    v, i = bs_ref.prune_pack(W, bank, k)
+    Y_ref = bs_ref.spmm(v, i, bank, X, threads=bs_ref.host_threads())
+    Y = host(bs.bs_spmm(dev(v), dev(i), bank, dev(X)))
+    err = bs_ref.rel_l2(Y, Y_ref)
+    say("  spmm relL2", err)
+    assert err <= tol
+    scale = np.abs(Y_ref).max() + 1e-30
+    assert np.abs(Y - Y_ref).max() <= tol * scale
+    return v, i, Y
+
+
+@pytest.mark.parametrize("M,K,bank,k", SMALL_SHAPES)
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 7, 8, 33, 130])
+def test_spmm_small(M, K, bank, k, N):
+    say("spmm small", M, K, bank, k, N)
+    W = workloads.draw_weights(M, K, 0.05, "f32", 35)
+    X = workloads.draw_activations(K, N, 35).reshape(K, N)
+    check_spmm(W, bank, k, X, 1e-5)
+
+
+@pytest.mark.parametrize("name", ["lstm1500_n8", "lstm1500_n32", "lstm1500_n128", "fc6_b16"])
+def test_spmm_full_size(name):
+    say("spmm full", name)
+    wl, W, X = workloads.make(name)
+    v, i, Y = check_spmm(W, wl.bank, wl.k, X, TOL[wl.dtype])
+    Y2 = host(bs.bs_spmm(dev(v), dev(i), wl.bank, dev(X)))
+    assert Y.tobytes() == Y2.tobytes()      # slab sums are added in a fixed order
+
+
+def test_spmm_n1_matches_spmv_and_f16_small():
+    wl, W, x = workloads.make("tiny")
+    v, i = bs_ref.prune_pack(W, wl.bank, wl.k)
+    Y = host(bs.bs_spmm(dev(v), dev(i), wl.bank, dev(x.reshape(-1, 1))))
+    assert bs_ref.rel_l2(Y[:, 0], bs_ref.spmv(v, i, wl.bank, x)) <= 1e-5
+    Wh = workloads.draw_weights(50, 1024, 0.01, "f16", 36)
+    X = workloads.draw_activations(1024, 16, 36)
+    check_spmm(Wh, 64, 6, X, 1e-2)
+
+
+def test_spmm_workspace_contract():
+    wl, W, X = workloads.make("lstm1500_n128", rows=64)
+    v, i = bs_ref.prune_pack(W, wl.bank, wl.k)
+    need = bs.bs_spmm_workspace_bytes(bs.BS_F32, 64, wl.K, wl.bank, wl.k, wl.N)
+    assert need > 0
+    small = torch.empty(need - 16, dtype=torch.uint8, device=DEV)
+    with pytest.raises(bs.BsError) as e:
+        bs.bs_spmm(dev(v), dev(i), wl.bank, dev(X), workspace=small)
+    assert e.value.status == 6
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    Y = host(bs.bs_spmm(dev(v), dev(i), wl.bank, dev(X), workspace=ws))
+    assert bs_ref.rel_l2(Y, bs_ref.spmm(v, i, wl.bank, X)) <= 1e-5
+
+
+# ------------------------------------------------------- dense baselines
+
+def close_to_scale(Y, Y_ref, W, X, tol):
+    """|error| <= tol * max_r sum_c |w_rc| |x_c|: an fp32 sum can lose that much
+    when terms cancel, so tiny outputs are judged against the size of the terms."""
+    scale = (np.abs(W.astype(np.float64)) @ np.abs(X.astype(np.float64))).max() + 1e-300
+    return np.abs(Y.astype(np.float64) - Y_ref).max() <= tol * scale
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("M,K", [(37, 300), (64, 1024), (130, 77), (1, 8)])
+def test_dense_baselines(dtype, M, K):
+    say("dense", dtype, M, K)
+    W = workloads.draw_weights(M, K, 0.05, dtype, 37)
+    x = workloads.draw_activations(K, 1, 37)
+    y_ref = bs_ref.dense_gemm_f64(W, x)
+    y = host(bs.bs_dense_gemv(dev(W), dev(x)))
+    assert close_to_scale(y, y_ref, W, x, 1e-5)
+    if M > 8:
+        assert bs_ref.rel_l2(y, y_ref.astype(np.float32)) <= 1e-5
+    for N in (1, 8, 20, 32, 100):
+        X = workloads.draw_activations(K, N, 38).reshape(K, N)
+        Y_ref = bs_ref.dense_gemm_f64(W, X)
+        Y = host(bs.bs_dense_gemm(dev(W), dev(X)))
+        assert close_to_scale(Y, Y_ref, W, X, 1e-5), N
+        if M > 8:
+            assert bs_ref.rel_l2(Y, Y_ref.astype(np.float32)) <= 1e-5, N
+
+
+def test_sparse_product_equals_dense_product_of_pruned_matrix_on_gpu():
+    """Eq. (2): the pruned layer is W_p . X; both GPU paths agree on it."""
+    wl, W, x = workloads.make("lstm1500", rows=512)
+    v, i = bs_ref.prune_pack(W, wl.bank, wl.k)
+    Wp = bs_ref.unpack(v, i, wl.bank)
+    y_s = host(bs.bs_spmv(dev(v), dev(i), wl.bank, dev(x)))
+    y_d = host(bs.bs_dense_gemv(dev(Wp), dev(x)))
+    assert bs_ref.rel_l2(y_s, y_d) <= 1e-5
+
+
+# ----------------------------------------------------- errors via the C-ABI
+
+def test_device_side_argument_errors():
+    v = torch.zeros((4, 2, 2), dtype=torch.float32, device=DEV)
+    i = torch.zeros((4, 2, 2), dtype=torch.uint8, device=DEV)
+    x = torch.zeros(8, device=DEV)
+    with pytest.raises(ValueError):
+        bs.bs_spmv(v, i, 4, torch.zeros(9, device=DEV))
+    with pytest.raises(TypeError):
+        bs.bs_spmv(v, i, 4, x.cpu())
+    base = torch.zeros(64, device=DEV)
+    with pytest.raises(bs.BsError) as e:           # x not 16-byte aligned
+        bs.bs_spmv(v, i, 4, base[1:9])
+    assert e.value.status == 4
+    y = bs.bs_spmv(v, i, 4, x)
+    assert host(y).tolist() == [0.0] * 4
