@@ -1,0 +1,319 @@
+#!/usr/bin/env python3
+"""Benchmark of the Balanced-Sparsity multiply on one MI355X.
+
+A step is one pass of the inference hot path over one synthetic batch: one
+``bs_spmv`` (or ``bs_spmm`` for workloads with N > 1) on the packed matrix,
+which ``bs_prune_pack`` wrote on the GPU before the timed region (pruning is a
+one-time, model-load step; it is timed separately and reported under
+``extras``).  The default workload is the LSTM-1500 gate matrix, 6000 x 3000,
+banks of 100 keeping 10 (90 % sparse), batch 1.
+
+Two regions of exactly K steps are timed:
+  * ``value``: algorithmic bytes x K / wall time between two HIP events on the
+    launch stream around the K launches (includes the gaps between launches);
+  * ``roofline.achieved``: algorithmic bytes / mean duration of the kernel
+    itself, from HIP events that receive each launch's own begin/end time
+    stamps (attaching those events slows the host side, hence a region of its own).
+"Cold" (default) rotates over enough copies of vals/idx to exceed twice the
+256 MB last-level cache, so every launch streams from HBM; ``--warm`` reuses one
+copy (cache resident; reported as such, never as HBM bandwidth).
+
+Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+LLC_BYTES = 256 << 20
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/);
+# None until measured for that workload.
+MEASURED_TRAFFIC = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="lstm1500")
+    ap.add_argument("--warm", action="store_true", help="reuse one copy of the matrix (cache resident)")
+    ap.add_argument("--eager", action="store_true", help="time Python-side launches, no HIP graph")
+    ap.add_argument("--no-extras", action="store_true", help="skip the secondary measurements")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    return ap.parse_args()
+
+
+class HipEvents:
+    """Raw hipEvent_t pairs, so single launches can be timed by their own time stamps."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float),
+                                                 ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            if self.hip.hipEventCreate(ctypes.byref(a)) or self.hip.hipEventCreate(ctypes.byref(b)):
+                raise RuntimeError("hipEventCreate failed")
+            self.pairs.append((a.value, b.value))
+
+    def us(self, i):
+        t = ctypes.c_float()
+        a, b = self.pairs[i]
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(t), ctypes.c_void_p(a), ctypes.c_void_p(b))
+        if rc:
+            raise RuntimeError(f"hipEventElapsedTime failed ({rc})")
+        return t.value * 1e3
+
+    def close(self):
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(ctypes.c_void_p(a))
+            self.hip.hipEventDestroy(ctypes.c_void_p(b))
+        self.pairs = []
+
+
+def region_us(torch, fn, n):
+    """Wall time per call of n back-to-back calls between two events on the launch stream."""
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    s.record()
+    for i in range(n):
+        fn(i)
+    e.record()
+    torch.cuda.synchronize()
+    return s.elapsed_time(e) * 1e3 / n
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 "
+              "(the path shards by rows, see DESIGN.md, but no multi-GPU code exists)",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_1811_00206_amd import binding as bs
+    from paper_1811_00206_amd import workloads
+
+    if not os.path.exists(bs.library_path()):
+        from paper_1811_00206_amd.build import build_library
+        build_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl, W, X = workloads.make(args.workload)
+    K, W_steps = args.steps, args.warmup
+    Wd = torch.from_numpy(W).to(dev)
+    Xd = torch.from_numpy(np.ascontiguousarray(X)).to(dev)
+    vals, idx = bs.bs_prune_pack(Wd, wl.bank, wl.k)        # the product path packs on the GPU
+    torch.cuda.synchronize()
+
+    alg_bytes = wl.spmv_bytes()
+    if args.warm:
+        R = 1
+    else:
+        R = max(2, -(-2 * LLC_BYTES // alg_bytes) + 1)
+    copies = [(vals, idx)] + [(vals.clone(), idx.clone()) for _ in range(R - 1)]
+    spmm = wl.N > 1
+    if spmm:
+        Y = torch.empty((wl.M, wl.N), dtype=torch.float32, device=dev)
+        ws_bytes = bs.bs_spmm_workspace_bytes(bs.BS_F16 if wl.dtype == "f16" else bs.BS_F32,
+                                              wl.M, wl.K, wl.bank, wl.k, wl.N)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    else:
+        Y = torch.empty(wl.M, dtype=torch.float32, device=dev)
+
+    events = None if spmm else HipEvents(K)
+    # arguments marshalled once per matrix copy: a step is then one C-ABI call
+    calls = None if spmm else [bs.PreparedSpmv(v, ix, wl.bank, Xd, Y) for v, ix in copies]
+
+    def step(i, timed=False):
+        if spmm:
+            v, ix = copies[i % R]
+            bs.bs_spmm(v, ix, wl.bank, Xd, out=Y, workspace=ws)
+        elif timed:
+            a, b = events.pairs[i]
+            calls[i % R](a, b)
+        else:
+            calls[i % R]()
+
+    for i in range(W_steps):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---- timed region A: exactly K steps between two events on the launch stream.
+    # The K launches are captured once into a HIP graph (the deployment form of a
+    # launch-bound loop) and replayed inside the region; --eager launches them
+    # from Python instead.
+    mode = "eager"
+    graph = None
+    if not args.eager:
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                if spmm:
+                    for i in range(K):
+                        step(i)
+                else:
+                    gcalls = [bs.PreparedSpmv(v, ix, wl.bank, Xd, Y) for v, ix in copies]
+                    for i in range(K):
+                        gcalls[i % R]()
+            graph.replay()                       # one untimed replay
+            torch.cuda.synchronize()
+            mode = "hip graph of K launches"
+        except Exception as exc:                 # capture unsupported: say so, time eagerly
+            print(f"bench.py: graph capture failed ({exc}); timing eager launches", file=sys.stderr)
+            graph = None
+    t_wall0 = time.perf_counter()
+    if graph is not None:
+        s_ev, e_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        s_ev.record()
+        graph.replay()
+        e_ev.record()
+        torch.cuda.synchronize()
+        us_per_step = s_ev.elapsed_time(e_ev) * 1e3 / K
+    else:
+        us_per_step = region_us(torch, step, K)
+    t_wall = time.perf_counter() - t_wall0
+
+    # ---- timed region B: the same K launches again, each with its own pair of
+    # events that receive the kernel's begin/end time stamps (kernel time only)
+    if spmm:
+        kern_us = us_per_step          # two kernels per step; no per-kernel stamps
+        kern_note = "region time per step (slab kernel + reduce kernel)"
+    else:
+        region_us(torch, lambda i: step(i, timed=True), K)
+        durs = np.array([events.us(i) for i in range(K)])
+        kern_us = float(durs.mean())
+        kern_note = "mean of per-launch kernel time stamps over K launches"
+    value = alg_bytes / us_per_step / 1e3                  # GB/s
+    achieved = alg_bytes / kern_us / 1e3
+
+    out = {
+        "metric": "bs_spmv achieved HBM GB/s" if not spmm else "bs_spmm achieved HBM GB/s",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W_steps,
+        "ms_per_step": round(us_per_step / 1e3, 6),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if wl.dtype == "f32" else "f16 storage, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: W {wl.M}x{wl.K} {wl.dtype}, bank {wl.bank}, keep {wl.k} "
+                               f"({100 * wl.sparsity:.3g}% sparse), batch {wl.N}",
+                   "residency": "warm (one copy, cache resident)" if args.warm else
+                                f"cold (rotating over {R} copies, {R * alg_bytes / 1e6:.0f} MB)",
+                   "launch": mode,
+                   "algorithmic_bytes_per_step": alg_bytes,
+                   "flop_per_step": wl.flops()},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC.get((wl.name, "warm" if args.warm else "cold")),
+                     "kernel_us": round(kern_us, 3), "how": kern_note},
+    }
+
+    extras = {"gflops": round(wl.flops() / us_per_step / 1e3, 1),
+              "host_wall_s_timed_region": round(t_wall, 3)}
+    if not spmm:
+        extras["kernel_us_min_med_p90"] = [round(float(v), 2) for v in
+                                           (durs.min(), np.median(durs), np.percentile(durs, 90))]
+
+    if not args.no_extras:
+        ev = HipEvents(64)
+
+        def kernel_us_of(v, ix, x, y, bank, n=64):
+            for i in range(n):
+                bs.bs_spmv(v, ix, bank, x, out=y, start_event=ev.pairs[i][0],
+                           stop_event=ev.pairs[i][1])
+            torch.cuda.synchronize()
+            return float(np.median([ev.us(i) for i in range(n)]))
+
+        # floor of the time-stamp method: a one-row matrix (nothing to stream)
+        v1 = torch.zeros((1, wl.nb, wl.k), dtype=vals.dtype, device=dev)
+        i1 = torch.zeros((1, wl.nb, wl.k), dtype=torch.uint8, device=dev)
+        y1 = torch.empty(1, dtype=torch.float32, device=dev)
+        if not spmm:
+            extras["launch_floor_us"] = round(kernel_us_of(v1, i1, Xd, y1, wl.bank), 2)
+            # the same matrix from cache (one copy): what an LSTM time step loop sees
+            w_us = kernel_us_of(vals, idx, Xd, Y, wl.bank)
+            extras["warm_kernel_us"] = round(w_us, 2)
+            extras["warm_GBps_cache_resident"] = round(alg_bytes / w_us / 1e3, 1)
+
+        def avg_us(fn, n):
+            for _ in range(3):
+                fn(0)
+            return region_us(torch, fn, n)
+
+        # dense baseline on the unpruned-shape matrix, same residency protocol
+        dense_bytes = wl.dense_bytes()
+        Rd = 1 if args.warm else max(2, -(-2 * LLC_BYTES // dense_bytes) + 1)
+        Wc = [Wd] + [Wd.clone() for _ in range(Rd - 1)]
+        if spmm:
+            d_us = avg_us(lambda i: bs.bs_dense_gemm(Wc[i % Rd], Xd, out=Y), 20)
+        else:
+            d_us = avg_us(lambda i: bs.bs_dense_gemv(Wc[i % Rd], Xd, out=Y), 200)
+        del Wc
+        extras["dense_us"] = round(d_us, 2)
+        extras["dense_GBps"] = round(dense_bytes / d_us / 1e3, 1)
+        extras["speedup_vs_dense"] = round(d_us / us_per_step, 2)   # both: region time per launch
+        # eq. (5) of the paper with the measured dense time and the measured launch floor
+        o_time = extras.get("launch_floor_us", 0.0)
+        extras["ideal_us_eq5"] = round((d_us - o_time) * (1 - wl.sparsity) + o_time, 2)
+        # one-time pruning + packing of the dense matrix
+        p_us = avg_us(lambda i: bs.bs_prune_pack(Wd, wl.bank, wl.k), 10)
+        p_bytes = W.nbytes + wl.nnz * (wl.val_bytes + 1)
+        extras["prune_pack_us"] = round(p_us, 1)
+        extras["prune_pack_GBps"] = round(p_bytes / p_us / 1e3, 1)
+        ev.close()
+    out["extras"] = extras
+
+    if not args.no_cpu:
+        from oracle import bs_ref
+        v_h, i_h = vals.cpu().numpy(), idx.cpu().numpy()
+        threads = min(16, bs_ref.host_threads())
+        fn = (lambda: bs_ref.spmm(v_h, i_h, wl.bank, X, threads=threads)) if spmm else \
+             (lambda: bs_ref.spmv(v_h, i_h, wl.bank, X, threads=threads))
+        fn()
+        t0 = time.perf_counter()
+        n_calls = 0
+        while True:
+            fn()
+            n_calls += 1
+            el = time.perf_counter() - t0
+            if el > 10.0 or n_calls >= 2000:
+                break
+        out["cpu_baseline"] = {"value": round(alg_bytes * n_calls / el / 1e9, 3), "unit": "GB/s",
+                               "cores": threads, "kind": "oracle",
+                               "sample": f"{n_calls} full products of the same workload "
+                                         f"in {el:.1f} s (fp64 accumulate, rows split over threads)",
+                               "us_per_call": round(el / n_calls * 1e6, 1)}
+    if events:
+        events.close()
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

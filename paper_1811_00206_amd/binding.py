@@ -177,6 +177,30 @@ def bs_spmv(vals, idx, bank: int, x, out=None, lanes_per_row: int = 0, rows_per_
     return y
 
 
+class PreparedSpmv:
+    """bs_spmv_ex with its arguments marshalled once, for launch loops where the
+    Python-side checks of :func:`bs_spmv` would dominate a microsecond kernel.
+    Each call is exactly one C-ABI call on the stream that was current at
+    construction; the tensors are kept alive by this object."""
+
+    def __init__(self, vals, idx, bank: int, x, out, lanes_per_row: int = 0, rows_per_wg: int = 0):
+        code, M, K, k = _packed(vals, idx, bank)
+        _dev(x, "x", torch.float32)
+        _dev(out, "out", torch.float32)
+        if x.numel() != K or out.numel() != M:
+            raise ValueError("x must have K elements and out M elements")
+        self._keep = (vals, idx, x, out)
+        self._fn = load_library().bs_spmv_ex
+        self._head = (_ptr(vals), _ptr(idx), code, M, K, bank, k, _ptr(x), _ptr(out),
+                      lanes_per_row, rows_per_wg)
+        self._stream = _stream()
+
+    def __call__(self, start_event: int = 0, stop_event: int = 0):
+        st = self._fn(*self._head, start_event, stop_event, self._stream)
+        if st:
+            raise BsError(st, "bs_spmv_ex")
+
+
 def bs_spmv_ex(vals, idx, bank, x, lanes_per_row, rows_per_wg, out=None, start_event=0,
                stop_event=0):
     return bs_spmv(vals, idx, bank, x, out=out, lanes_per_row=lanes_per_row,

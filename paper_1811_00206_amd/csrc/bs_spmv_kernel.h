@@ -1,0 +1,259 @@
+// y = W_sparse . x for a Balanced-Sparsity matrix (arXiv 1811.00206, Sec. 3.4,
+// batch size 1; eq. (1) with zero bias; Fig. 3: x is read at bank base + offset).
+//
+// Design for gfx950.  The product is bound by streaming vals+idx from HBM once
+// (5 bytes per stored weight in fp32, 3 in binary16), and for the matrices of
+// interest the kernel lasts a few microseconds, so it is built around putting
+// all of a workgroup's bytes in flight before anything waits, and around a
+// short dependent chain after they arrive:
+//   * a row's stored entries are one contiguous run of nb*k values and nb*k
+//     offset bytes; LPR lanes of one wavefront share a row and walk it in
+//     16-byte value chunks (CH entries) with a stride of LPR chunks, so every
+//     load instruction of a wavefront reads whole contiguous segments;
+//   * each wavefront first issues its share of x as direct-to-LDS loads, then
+//     every lane issues up to U value loads and U offset loads, back to back;
+//     x (small, cache resident) lands first, while the weights are still in flight;
+//   * x is gathered from LDS at bank*B + offset (lane-local addresses; the
+//     paper's shared-memory staging, but without its lane<->bank binding:
+//     LDS gather bandwidth is several times the HBM stream here); the code
+//     after the barrier is straight-line: no per-chunk branches, one partial
+//     sum per chunk slot;
+//   * the LPR partial sums of a row are combined with DPP moves; lane 0 of the
+//     group stores y[r].  No atomics, fixed summation order.
+// The paper's kernel gives one thread a whole bank; here a lane owns chunks of
+// the flat stream instead, because per-bank lanes would read HBM with a
+// k*sizeof stride.
+#pragma once
+#include "bs_internal.h"
+
+namespace bs {
+
+struct SpmvArgs {
+    const void* vals;
+    const uint8_t* idx;
+    const float* x;
+    float* y;
+    int M;
+    int K;
+    int B;
+    int k;
+    uint32_t magic_k;       // magic_u32(k)
+    int row_len;            // nb * k entries per row
+    int chunks_per_row;     // row_len / CH
+    int rows_per_wg;
+    int bank_mode;          // 0: k % CH == 0 (a chunk never leaves its bank)
+                            // 1: k >= CH (a chunk touches at most two banks)
+                            // 2: anything else
+};
+
+struct SpmvLaunch {
+    int threads;
+    int grid;
+    size_t lds;
+    hipEvent_t ev_start, ev_stop;   // optional: the kernel's own begin/end time stamps
+    hipStream_t st;
+};
+
+// launchers instantiated per storage type (one translation unit each)
+int spmv_launch_f32(int ch, int lpr, int u, const SpmvArgs& a, const SpmvLaunch& l);
+int spmv_launch_f16(int ch, int lpr, int u, const SpmvArgs& a, const SpmvLaunch& l);
+
+#ifdef __HIPCC__
+
+// s_waitcnt: at most N vector-memory loads outstanding, no LDS/scalar operation
+// outstanding (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 left at
+// its maximum, lgkmcnt 11:8).
+template <int N>
+__device__ __forceinline__ void wait_vm_and_lds() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 0xf) | (0x7 << 4) | (0x0 << 8) | (((N >> 4) & 0x3) << 14));
+}
+
+// Nothing that touches memory moves across this point, neither in the
+// optimiser nor in the instruction scheduler.
+__device__ __forceinline__ void pin_order() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// Sum over the U chunk slots a lane holds in registers.  Slot u is chunk
+// c0 + u*LPR of the row; slots past the end of the row hold a re-read of the
+// row's last chunk (valid memory) and are masked out here.  MODE as in
+// SpmvArgs::bank_mode.  Straight-line code: no branch depends on a lane.
+template <typename VT, int CH, int LPR, int U, int MODE, typename VRaw, typename IRaw>
+__device__ __forceinline__ float consume(const SpmvArgs& a, const float* xs, const VRaw (&v)[U],
+                                         const IRaw (&o)[U], int c0, int cpr) {
+    float part[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int c = c0 + u * LPR;
+        const bool ok = c < cpr;
+        // first entry of the chunk: which bank, and where inside it (entry 0 of the
+        // row for a masked slot, so every LDS address below stays inside x)
+        const uint32_t e = ok ? (uint32_t)c * CH : 0u;
+        const uint32_t bank = div_magic(e, (uint32_t)a.k, a.magic_k);
+        const uint32_t pos = e - bank * a.k;
+        const uint32_t xb = bank * a.B;
+        float p = 0.f;
+        if constexpr (MODE == 0) {
+#pragma unroll
+            for (int i = 0; i < CH; ++i)
+                p = fmaf(value_at<VT>(v[u], i), xs[xb + offset_at(o[u], i)], p);
+        } else if constexpr (MODE == 1) {
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+                const uint32_t step = (pos + i >= (uint32_t)a.k) ? (uint32_t)a.B : 0u;
+                p = fmaf(value_at<VT>(v[u], i), xs[xb + step + offset_at(o[u], i)], p);
+            }
+        } else {
+            uint32_t q = pos, b = xb;
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+                p = fmaf(value_at<VT>(v[u], i), xs[b + offset_at(o[u], i)], p);
+                ++q;
+                if (q == (uint32_t)a.k) { q = 0; b += a.B; }
+            }
+        }
+        part[u] = ok ? p : 0.f;
+    }
+    float acc = part[0];
+#pragma unroll
+    for (int u = 1; u < U; ++u) acc += part[u];
+    return acc;
+}
+
+template <typename VT, int CH, int LPR, int U, typename VRaw, typename IRaw>
+__device__ __forceinline__ float consume_any(const SpmvArgs& a, const float* xs,
+                                             const VRaw (&v)[U], const IRaw (&o)[U], int c0,
+                                             int cpr) {
+    // bank_mode is the same for every lane of the grid: a scalar branch
+    if (a.bank_mode == 0) return consume<VT, CH, LPR, U, 0>(a, xs, v, o, c0, cpr);
+    if (a.bank_mode == 1) return consume<VT, CH, LPR, U, 1>(a, xs, v, o, c0, cpr);
+    return consume<VT, CH, LPR, U, 2>(a, xs, v, o, c0, cpr);
+}
+
+// VT: storage type of vals; CH: entries per chunk (CH*sizeof(VT) <= 16, CH divides
+// row_len); LPR: lanes per row; U: chunks a lane keeps in flight per round.
+template <typename VT, int CH, int LPR, int U>
+__global__ __launch_bounds__(1024) void spmv_kernel(SpmvArgs a) {
+    extern __shared__ __align__(16) float xs[];
+    using VRaw = typename RawBytes<CH * sizeof(VT)>::type;
+    using IRaw = typename RawBytes<CH>::type;
+    const int tid = threadIdx.x;
+    const int nthr = blockDim.x;
+    const int lane_in_row = tid % LPR;
+    const int row_in_wg = tid / LPR;
+    const int row = blockIdx.x * a.rows_per_wg + row_in_wg;
+    const bool live = row < a.M;
+    const int rowc = live ? row : a.M - 1;   // clamp: dead lanes load valid memory
+
+    const VRaw* vrow = reinterpret_cast<const VRaw*>(
+        static_cast<const VT*>(a.vals) + (size_t)rowc * a.row_len);
+    const IRaw* irow = reinterpret_cast<const IRaw*>(a.idx + (size_t)rowc * a.row_len);
+    const int cpr = a.chunks_per_row;
+
+    // (1) x -> LDS with direct-to-LDS loads: each wavefront copies 1 KB pieces
+    // (64 lanes x 16 bytes) without passing through registers.  They are issued
+    // before the weight loads and memory returns loads in order, so waiting until
+    // at most the 2*U weight loads are outstanding means x has landed.
+    const int K4 = a.K >> 2;
+    for (int i = (K4 << 2) + tid; i < a.K; i += nthr) xs[i] = a.x[i];   // K % 4 tail
+    {
+        const float4* x4 = reinterpret_cast<const float4*>(a.x);
+        const int wave = tid >> 6, lane = tid & 63, n_waves = nthr >> 6;
+        for (int p = wave; p * 64 < K4; p += n_waves) {
+            const int i = p * 64 + lane;
+            if (i < K4)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(x4 + i),
+                    (__attribute__((address_space(3))) void*)(xs + p * 256), 16, 0, 0);
+        }
+    }
+
+    pin_order();
+
+    // (2) round 0 of the weight stream, everything in flight behind x.  The loads
+    // are unconditional with a clamped chunk number (an in-range re-read instead of
+    // a skipped load), so they are emitted back to back: exactly 2*U of them
+    // between the two pins (the build checks this in the generated code).
+    VRaw v[U];
+    IRaw o[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int c = min(lane_in_row + u * LPR, cpr - 1);
+        v[u] = vrow[c];
+        o[u] = irow[c];
+    }
+    pin_order();
+
+    // (3) wait for this wavefront's part of x (not for the weights), then for
+    // everyone else's.  A plain barrier: __syncthreads() would add a fence that
+    // drains the weight loads too.
+    wait_vm_and_lds<2 * U>();
+    __builtin_amdgcn_s_barrier();
+    pin_order();
+
+    // (4) gather-multiply-add, then further rounds for rows longer than LPR*U chunks
+    float acc = consume_any<VT, CH, LPR, U>(a, xs, v, o, lane_in_row, cpr);
+    for (int c0 = lane_in_row + U * LPR; c0 - lane_in_row < cpr; c0 += U * LPR) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = min(c0 + u * LPR, cpr - 1);
+            v[u] = vrow[c];
+            o[u] = irow[c];
+        }
+        acc += consume_any<VT, CH, LPR, U>(a, xs, v, o, c0, cpr);
+    }
+
+    acc = group_sum<LPR>(acc);
+    if (live && lane_in_row == 0) a.y[row] = acc;
+}
+
+template <typename VT, int CH, int LPR, int U>
+int spmv_launch_one(const SpmvArgs& a, const SpmvLaunch& l) {
+    auto kern = spmv_kernel<VT, CH, LPR, U>;
+    if (l.lds > 48 * 1024) {
+        static bool raised = false;   // per instantiation; raising it twice is harmless
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               kMaxLdsBytes);
+            if (e != hipSuccess) return BS_ERR_HIP;
+            raised = true;
+        }
+    }
+    if (l.ev_start || l.ev_stop)
+        hipExtLaunchKernelGGL(kern, dim3(l.grid), dim3(l.threads), l.lds, l.st, l.ev_start,
+                              l.ev_stop, 0, a);
+    else
+        hipLaunchKernelGGL(kern, dim3(l.grid), dim3(l.threads), l.lds, l.st, a);
+    return hip_status(hipGetLastError());
+}
+
+template <typename VT, int CH, int LPR>
+int spmv_launch_u(int u, const SpmvArgs& a, const SpmvLaunch& l) {
+    switch (u) {
+        case 2: return spmv_launch_one<VT, CH, LPR, 2>(a, l);
+        case 4: return spmv_launch_one<VT, CH, LPR, 4>(a, l);
+        case 6: return spmv_launch_one<VT, CH, LPR, 6>(a, l);
+        case 8: return spmv_launch_one<VT, CH, LPR, 8>(a, l);
+    }
+    return BS_ERR_UNSUPPORTED;
+}
+
+template <typename VT, int CH>
+int spmv_launch_lpr(int lpr, int u, const SpmvArgs& a, const SpmvLaunch& l) {
+    switch (lpr) {
+        case 1: return spmv_launch_u<VT, CH, 1>(u, a, l);
+        case 2: return spmv_launch_u<VT, CH, 2>(u, a, l);
+        case 4: return spmv_launch_u<VT, CH, 4>(u, a, l);
+        case 8: return spmv_launch_u<VT, CH, 8>(u, a, l);
+        case 16: return spmv_launch_u<VT, CH, 16>(u, a, l);
+        case 32: return spmv_launch_u<VT, CH, 32>(u, a, l);
+        case 64: return spmv_launch_u<VT, CH, 64>(u, a, l);
+    }
+    return BS_ERR_UNSUPPORTED;
+}
+
+#endif  // __HIPCC__
+}  // namespace bs

@@ -1,0 +1,93 @@
+"""Build-time check of an assumption the SpMV kernel makes about its own
+generated code.
+
+The kernel copies x into LDS with direct-to-LDS loads, then issues the weight
+loads, then waits with ``s_waitcnt vmcnt(N)`` before a plain ``s_barrier``.
+Loads complete in issue order, so the wait covers the copy of x exactly when at
+least N vector-memory loads were issued after the last direct-to-LDS load.
+The compiler does not track that dependency itself, so this test reads the
+assembly the compiler emits for OUR sources (``hipcc -S``) and checks N against
+the instruction stream of every instantiation.  No GPU needed.
+"""
+import os
+import re
+import subprocess
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
+
+import pytest
+
+from paper_1811_00206_amd import build as bs_build
+
+SOURCES = ["bs_spmv_f32.hip", "bs_spmv_f16.hip"]
+
+
+def _assembly(src):
+    out = tempfile.NamedTemporaryFile(suffix=".s", delete=False).name
+    flags = [f for f in bs_build.FLAGS if f not in ("-fPIC",)]
+    subprocess.check_call([bs_build.HIPCC, *flags, "-S", "--cuda-device-only", "-o", out,
+                           os.path.join(bs_build.CSRC, src)],
+                          stderr=subprocess.DEVNULL)
+    text = open(out).read()
+    os.unlink(out)
+    return text
+
+
+def _kernels(text):
+    """name -> list of instruction lines, for every spmv_kernel instantiation."""
+    out = {}
+    cur = None
+    for line in text.splitlines():
+        m = re.match(r"^(_ZN2bs11spmv_kernel\w+):", line)
+        if m:
+            cur = m.group(1)
+            out[cur] = []
+            continue
+        if cur is not None:
+            s = line.strip()
+            if s.startswith("s_endpgm"):
+                cur = None
+            elif s and not s.startswith((";", ".")):
+                out[cur].append(s)
+    return out
+
+
+def _is_vmem_load(ins):
+    return ins.startswith(("global_load_", "buffer_load_", "flat_load_", "scratch_load_"))
+
+
+@pytest.fixture(scope="module")
+def kernels():
+    with ThreadPoolExecutor(2) as ex:
+        texts = list(ex.map(_assembly, SOURCES))
+    ks = {}
+    for t in texts:
+        ks.update(_kernels(t))
+    return ks
+
+
+def test_every_instantiation_is_present(kernels):
+    # 3 chunk widths for fp32 + 4 for fp16, 7 group widths, 4 in-flight depths
+    assert len(kernels) == (3 + 4) * 7 * 4
+
+
+def test_wait_before_barrier_covers_the_copy_of_x(kernels):
+    for name, ins in kernels.items():
+        barrier = next(i for i, s in enumerate(ins) if s.startswith("s_barrier"))
+        dma = [i for i, s in enumerate(ins[:barrier]) if s.startswith("global_load_lds")]
+        assert dma, f"{name}: no direct-to-LDS load before the barrier"
+        last_dma = dma[-1]
+        waits = [i for i in range(last_dma, barrier) if ins[i].startswith("s_waitcnt")
+                 and "vmcnt" in ins[i]]
+        assert waits, f"{name}: no vmcnt wait between the copy of x and the barrier"
+        w = waits[-1]
+        n_allowed = int(re.search(r"vmcnt\((\d+)\)", ins[w]).group(1))
+        issued_after = sum(_is_vmem_load(s) and not s.startswith("global_load_lds")
+                           for s in ins[last_dma + 1:w])
+        assert n_allowed <= issued_after, (
+            f"{name}: waits for vmcnt({n_allowed}) but only {issued_after} loads follow the "
+            "last direct-to-LDS load: x may not have landed at the barrier")
+        # nothing that reads LDS may sit between that wait and the barrier
+        assert not any(s.startswith("ds_read") for s in ins[w:barrier]), name
+        # and no LDS read of x before the barrier at all
+        assert not any(s.startswith("ds_read") for s in ins[:barrier]), name
