@@ -6,10 +6,17 @@ namespace bs {
 int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
                 int k, const float* x, float* y, int lanes_per_row, int rows_per_wg,
                 hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st) {
-    const size_t lds = (size_t)K * sizeof(float);
+    const int64_t row_len = (K / bank) * k;
+    // LDS: x, then (if it fits) one word per row entry for the bank table
+    const size_t x_floats = ((size_t)K + 3) / 4 * 4;
+    size_t lds = x_floats * sizeof(float);
     if (lds > (size_t)kMaxLdsBytes) return BS_ERR_UNSUPPORTED;   // x must fit in one CU's LDS
     if (M > INT32_MAX) return BS_ERR_UNSUPPORTED;
-    const int64_t row_len = (K / bank) * k;
+    int table_off = 0;
+    if (lds + (size_t)row_len * 4 <= (size_t)kMaxLdsBytes) {
+        table_off = (int)x_floats;
+        lds += (size_t)row_len * 4;
+    }
     const int vsize = dtype == BS_F16 ? 2 : 4;
 
     // widest chunk that divides the row, so chunks never straddle rows and stay aligned
@@ -34,7 +41,7 @@ int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int6
     int rpw = rows_per_wg;
     if (rpw == 0) {
         // 256 lanes per workgroup; 1024 when x is large, so fewer copies of x are staged
-        int threads = lds > 32 * 1024 ? 1024 : 256;
+        int threads = x_floats * 4 > 32 * 1024 ? 1024 : 256;
         rpw = threads / lpr;
     }
     const int64_t threads = (int64_t)lpr * rpw;
@@ -50,6 +57,7 @@ int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int6
     a.chunks_per_row = (int)cpr;
     a.rows_per_wg = rpw;
     a.bank_mode = (k % ch == 0) ? 0 : (k >= ch ? 1 : 2);
+    a.table_off = table_off;
 
     const SpmvLaunch l{(int)threads, (int)grid, lds, ev_start, ev_stop, st};
     if (dtype == BS_F16) return spmv_launch_f16(ch, lpr, u, a, l);

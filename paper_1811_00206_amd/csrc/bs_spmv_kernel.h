@@ -41,9 +41,12 @@ struct SpmvArgs {
     int row_len;            // nb * k entries per row
     int chunks_per_row;     // row_len / CH
     int rows_per_wg;
-    int bank_mode;          // 0: k % CH == 0 (a chunk never leaves its bank)
+    int bank_mode;          // how the arithmetic path finds the bank of an entry:
+                            // 0: k % CH == 0 (a chunk never leaves its bank)
                             // 1: k >= CH (a chunk touches at most two banks)
                             // 2: anything else
+    int table_off;          // > 0: float index in LDS of the per-entry bank table
+                            // (row_len words behind x); 0: no table, arithmetic path
 };
 
 struct SpmvLaunch {
@@ -122,11 +125,57 @@ __device__ __forceinline__ float consume(const SpmvArgs& a, const float* xs, con
     return acc;
 }
 
+// Same sum with the bank table: tab[e] holds the LDS byte offset of the x slice
+// of the bank that entry e of a row belongs to (identical for every row, built
+// once per workgroup), so an entry costs one shift-and-add besides the gather
+// and the multiply-add, whatever k and the chunk width are.
+template <typename VT, int CH, int LPR, int U, typename VRaw, typename IRaw>
+__device__ __forceinline__ float consume_table(const float* xs, const uint32_t* tab,
+                                               const VRaw (&v)[U], const IRaw (&o)[U], int c0,
+                                               int cpr) {
+    float part[U];
+    const char* xbytes = reinterpret_cast<const char*>(xs);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int c = c0 + u * LPR;
+        const bool ok = c < cpr;
+        const uint32_t* t = tab + (ok ? c : 0) * CH;
+        uint32_t base[CH];
+        if constexpr (CH >= 4) {
+#pragma unroll
+            for (int q = 0; q < CH / 4; ++q) {
+                const uint4 w = reinterpret_cast<const uint4*>(t)[q];
+                base[4 * q] = w.x; base[4 * q + 1] = w.y; base[4 * q + 2] = w.z; base[4 * q + 3] = w.w;
+            }
+        } else if constexpr (CH == 2) {
+            const uint2 w = *reinterpret_cast<const uint2*>(t);
+            base[0] = w.x; base[1] = w.y;
+        } else {
+            base[0] = t[0];
+        }
+        float p = 0.f;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const float xv =
+                *reinterpret_cast<const float*>(xbytes + base[i] + (offset_at(o[u], i) << 2));
+            p = fmaf(value_at<VT>(v[u], i), xv, p);
+        }
+        part[u] = ok ? p : 0.f;
+    }
+    float acc = part[0];
+#pragma unroll
+    for (int u = 1; u < U; ++u) acc += part[u];
+    return acc;
+}
+
 template <typename VT, int CH, int LPR, int U, typename VRaw, typename IRaw>
 __device__ __forceinline__ float consume_any(const SpmvArgs& a, const float* xs,
                                              const VRaw (&v)[U], const IRaw (&o)[U], int c0,
                                              int cpr) {
-    // bank_mode is the same for every lane of the grid: a scalar branch
+    // table_off and bank_mode are the same for every lane of the grid: scalar branches
+    if (a.table_off > 0)
+        return consume_table<VT, CH, LPR, U>(
+            xs, reinterpret_cast<const uint32_t*>(xs + a.table_off), v, o, c0, cpr);
     if (a.bank_mode == 0) return consume<VT, CH, LPR, U, 0>(a, xs, v, o, c0, cpr);
     if (a.bank_mode == 1) return consume<VT, CH, LPR, U, 1>(a, xs, v, o, c0, cpr);
     return consume<VT, CH, LPR, U, 2>(a, xs, v, o, c0, cpr);
@@ -185,6 +234,13 @@ __global__ __launch_bounds__(1024) void spmv_kernel(SpmvArgs a) {
         o[u] = irow[c];
     }
     pin_order();
+
+    // (2b) while all of that flies: the bank table (see consume_table)
+    if (a.table_off > 0) {
+        uint32_t* tab = reinterpret_cast<uint32_t*>(xs + a.table_off);
+        for (int e = tid; e < a.row_len; e += nthr)
+            tab[e] = __umul24(div_magic((uint32_t)e, (uint32_t)a.k, a.magic_k), (uint32_t)a.B) << 2;
+    }
 
     // (3) wait for this wavefront's part of x (not for the weights), then for
     // everyone else's.  A plain barrier: __syncthreads() would add a fence that
