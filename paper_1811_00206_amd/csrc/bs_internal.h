@@ -68,6 +68,38 @@ __device__ __forceinline__ float group_sum(float v) {
     return v;
 }
 
+// integer versions: sum over the group, and sum over the lanes of the group
+// below the calling lane (exclusive prefix)
+template <int CTRL>
+__device__ __forceinline__ int dpp_move_i(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+
+template <int W>
+__device__ __forceinline__ int group_sum_i(int v) {
+    static_assert(W >= 1 && W <= 64 && (W & (W - 1)) == 0, "group width");
+    if constexpr (W >= 2) v += dpp_move_i<0xB1>(v);
+    if constexpr (W >= 4) v += dpp_move_i<0x4E>(v);
+    if constexpr (W >= 8) v += dpp_move_i<0x141>(v);
+    if constexpr (W >= 16) v += dpp_move_i<0x140>(v);
+    if constexpr (W >= 32) v += __shfl_xor(v, 16, 64);
+    if constexpr (W >= 64) v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
+// q = lane's position inside its group of W lanes
+template <int W>
+__device__ __forceinline__ int group_prefix_i(int v, int q) {
+    int incl = v;
+    if constexpr (W >= 2) { int t = dpp_move_i<0x111>(incl); if (q >= 1) incl += t; }   // row_shr:1
+    if constexpr (W >= 4) { int t = dpp_move_i<0x112>(incl); if (q >= 2) incl += t; }   // row_shr:2
+    if constexpr (W >= 8) { int t = dpp_move_i<0x114>(incl); if (q >= 4) incl += t; }   // row_shr:4
+    if constexpr (W >= 16) { int t = dpp_move_i<0x118>(incl); if (q >= 8) incl += t; }  // row_shr:8
+    if constexpr (W >= 32) { int t = __shfl_up(incl, 16, 64); if (q >= 16) incl += t; }
+    if constexpr (W >= 64) { int t = __shfl_up(incl, 32, 64); if (q >= 32) incl += t; }
+    return incl - v;
+}
+
 // number of set bits of `mask` below the calling lane
 __device__ __forceinline__ int lanes_below(uint64_t mask) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
