@@ -151,6 +151,22 @@ __device__ __forceinline__ T zero_raw() {
     return z;
 }
 
+// s_waitcnt: at most N vector-memory loads outstanding, no LDS/scalar operation
+// outstanding (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 left at
+// its maximum, lgkmcnt 11:8).
+template <int N>
+__device__ __forceinline__ void wait_vm_and_lds() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 0xf) | (0x7 << 4) | (0x0 << 8) | (((N >> 4) & 0x3) << 14));
+}
+
+// Nothing that touches memory moves across this point, neither in the
+// optimiser nor in the instruction scheduler.
+__device__ __forceinline__ void pin_order() {
+    asm volatile("; bs_pin" ::: "memory");   // the comment marks the spot in the assembly
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 #endif  // __HIPCC__
 
 }  // namespace bs

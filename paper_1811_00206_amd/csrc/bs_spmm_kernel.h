@@ -1,0 +1,300 @@
+// Y = W_sparse . X for a Balanced-Sparsity matrix and a K x N activation matrix
+// (arXiv 1811.00206, Sec. 3.4 with batch size > 1; Sec. 4.1 "batchsize = 8";
+// convolution as im2col matrix-matrix product, Sec. 4.2).
+//
+// Every loaded (value, offset) pair is reused across the columns of X.  Rows
+// share no gathered operand (each row's offsets differ), so this is not a dense
+// contraction: every multiply-add needs one X operand from a data-dependent
+// row, and the floor is LDS gather bandwidth once N is large.  The kernel keeps
+// the SpMV structure and widens the gather:
+//   * the work is cut into tiles: a slab of `sb` consecutive banks x `nt`
+//     columns of X (sb*B rows of nl*4 floats) is copied into LDS with
+//     direct-to-LDS loads; a workgroup owns one tile and a range of rows;
+//   * within a wavefront LPR lanes share a (row, column group) and walk the
+//     row's entries of the slab in 16-byte value chunks, nl column groups of 4
+//     columns sit side by side, and the remaining lanes take further rows; an
+//     entry costs one 16-byte LDS read and four multiply-adds per lane;
+//   * the LDS address of an entry comes from a per-workgroup table
+//     (position in the slab -> byte offset of its bank's rows), as in SpMV;
+//   * the chunks of the next row pass are loaded while the current pass is
+//     consumed (two register sets);
+//   * the LPR partial sums are combined with DPP moves; with more than one slab
+//     the slab results go to a workspace and a second kernel adds them in slab
+//     order, so results do not depend on scheduling;
+//   * workgroups that share a tile get consecutive numbers after an XCD-aware
+//     remap, so the tile of X is fetched into one XCD's L2.
+#pragma once
+#include "bs_internal.h"
+
+namespace bs {
+
+constexpr int kXcds = 8;
+
+struct SpmmArgs {
+    const void* vals;
+    const uint8_t* idx;
+    const float* X;
+    float* out;            // Y (one slab) or the workspace [n_slabs][M][N]
+    int64_t ldx;
+    int64_t ld_out;        // ldy, or N for the workspace
+    int64_t slab_stride;   // M*N for the workspace, 0 for Y
+    int M, K, B, k, N;
+    int nb;
+    int sb, n_slabs;       // banks per slab
+    int nt, n_tiles;       // columns per tile
+    int nl;                // column groups (of 4) per tile: 1, 2, 4, 8 or 16
+    int rows_per_wg, row_groups;
+    int total_wgs, wgs_per_xcd;
+    int table_off;         // float index in LDS of the position table
+    uint32_t magic_k;
+    int dma;               // tile rows can be copied with 16-byte direct-to-LDS loads
+};
+
+struct SpmmLaunch {
+    int threads;
+    size_t lds;
+    hipStream_t st;
+};
+
+int spmm_launch_f32(int ch, int lpr, int u, const SpmmArgs& a, const SpmmLaunch& l);
+int spmm_launch_f16(int ch, int lpr, int u, const SpmmArgs& a, const SpmmLaunch& l);
+
+#ifdef __HIPCC__
+
+// Four column sums over the U chunk slots a lane holds; slot u is chunk c0 + u*LPR
+// of the row's run inside the slab (`cps` chunks).  xcol points at the lane's 4
+// columns of LDS row 0; pitch = bytes per LDS row.
+template <typename VT, int CH, int LPR, int U, typename VRaw, typename IRaw>
+__device__ __forceinline__ void spmm_consume(const char* xcol, const uint32_t* tab, uint32_t pitch,
+                                             const VRaw (&v)[U], const IRaw (&o)[U], int c0,
+                                             int cps, float (&acc)[4]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int c = c0 + u * LPR;
+        const bool ok = c < cps;
+        const uint32_t* t = tab + (ok ? c : 0) * CH;
+        uint32_t base[CH];
+        if constexpr (CH >= 4) {
+#pragma unroll
+            for (int q = 0; q < CH / 4; ++q) {
+                const uint4 w = reinterpret_cast<const uint4*>(t)[q];
+                base[4 * q] = w.x; base[4 * q + 1] = w.y; base[4 * q + 2] = w.z; base[4 * q + 3] = w.w;
+            }
+        } else if constexpr (CH == 2) {
+            const uint2 w = *reinterpret_cast<const uint2*>(t);
+            base[0] = w.x; base[1] = w.y;
+        } else {
+            base[0] = t[0];
+        }
+        float p[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const float w = value_at<VT>(v[u], i);
+            const float4 xv = *reinterpret_cast<const float4*>(
+                xcol + base[i] + __umul24(offset_at(o[u], i), pitch));
+            p[0] = fmaf(w, xv.x, p[0]);
+            p[1] = fmaf(w, xv.y, p[1]);
+            p[2] = fmaf(w, xv.z, p[2]);
+            p[3] = fmaf(w, xv.w, p[3]);
+        }
+#pragma unroll
+        for (int n = 0; n < 4; ++n) acc[n] += ok ? p[n] : 0.f;
+    }
+}
+
+template <typename VT, int CH, int LPR, int U>
+__global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
+    extern __shared__ __align__(16) float Xs[];
+    using VRaw = typename RawBytes<CH * sizeof(VT)>::type;
+    using IRaw = typename RawBytes<CH>::type;
+
+    // workgroup number -> (tile, slab, row group); consecutive numbers share an XCD
+    const int b = blockIdx.x;
+    const int wg = (b % kXcds) * a.wgs_per_xcd + b / kXcds;
+    if (wg >= a.total_wgs) return;
+    const int g = wg % a.row_groups;
+    const int s = (wg / a.row_groups) % a.n_slabs;
+    const int z = wg / (a.row_groups * a.n_slabs);
+
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int j0 = s * a.sb;
+    const int banks = min(a.sb, a.nb - j0);
+    const int n0 = z * a.nt;
+    const int ntw = min(a.nt, a.N - n0);          // live columns of this tile
+    const int nl = a.nl;
+    const uint32_t pitch = (uint32_t)nl * 16u;    // bytes per LDS row
+    const int slab_rows = banks * a.B;
+    const int seg = banks * a.k;                  // entries of one row inside the slab
+    const int cps = seg / CH;                     // exact by construction of the plan
+
+    // lane -> (row slot, column group, lane in the chunk walk)
+    const int l = tid % LPR;
+    const int cg = (tid / LPR) % nl;
+    const int slot = tid / (LPR * nl);
+    const int rows_per_pass = nthr / (LPR * nl);
+    const int r_begin = g * a.rows_per_wg;
+    const int r_end = min(a.M, r_begin + a.rows_per_wg);
+
+    // (1) the tile of X -> LDS
+    const float* Xg = a.X + (size_t)j0 * a.B * a.ldx + n0;
+    const int total_f4 = slab_rows * nl;
+    if (a.dma) {
+        const int wave = tid >> 6, lane = tid & 63, n_waves = nthr >> 6;
+        for (int p = wave; p * 64 < total_f4; p += n_waves) {
+            const int i = p * 64 + lane;
+            if (i < total_f4) {
+                const int r = i / nl, c4 = i - r * nl;
+                // columns past the tile's live width are never read back as results
+                const float* src = Xg + (size_t)r * a.ldx + min(c4 * 4, max(ntw - 4, 0));
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)src,
+                    (__attribute__((address_space(3))) void*)(Xs + p * 256), 16, 0, 0);
+            }
+        }
+    } else {
+        for (int i = tid; i < total_f4; i += nthr) {
+            const int r = i / nl, c4 = i - r * nl;
+            const float* src = Xg + (size_t)r * a.ldx + c4 * 4;
+            float4 t;
+            t.x = c4 * 4 + 0 < ntw ? src[0] : 0.f;
+            t.y = c4 * 4 + 1 < ntw ? src[1] : 0.f;
+            t.z = c4 * 4 + 2 < ntw ? src[2] : 0.f;
+            t.w = c4 * 4 + 3 < ntw ? src[3] : 0.f;
+            reinterpret_cast<float4*>(Xs)[i] = t;
+        }
+    }
+    pin_order();
+
+    // (2) first pass of the weight stream: exactly 2*U loads between the pins
+    const VT* vbase = static_cast<const VT*>(a.vals);
+    VRaw vA[U], vB[U];
+    IRaw oA[U], oB[U];
+    auto row_ptrs = [&](int r, const VRaw*& vrow, const IRaw*& irow) {
+        const int rc = min(r, a.M - 1);
+        const size_t e0 = ((size_t)rc * a.nb + j0) * a.k;
+        vrow = reinterpret_cast<const VRaw*>(vbase + e0);
+        irow = reinterpret_cast<const IRaw*>(a.idx + e0);
+    };
+    int r = r_begin + slot;
+    {
+        const VRaw* vrow; const IRaw* irow;
+        row_ptrs(r, vrow, irow);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = min(l + u * LPR, cps - 1);
+            vA[u] = vrow[c];
+            oA[u] = irow[c];
+        }
+    }
+    pin_order();
+
+    // (2b) position table: byte offset of the LDS rows of the bank an entry is in
+    uint32_t* tab = reinterpret_cast<uint32_t*>(Xs + a.table_off);
+    for (int e = tid; e < seg; e += nthr)
+        tab[e] = __umul24(__umul24(div_magic((uint32_t)e, (uint32_t)a.k, a.magic_k), (uint32_t)a.B), pitch);
+
+    // (3) wait for this wavefront's share of X (not for the weights), then everyone's
+    wait_vm_and_lds<2 * U>();
+    __builtin_amdgcn_s_barrier();
+    pin_order();
+
+    const char* xcol = reinterpret_cast<const char*>(Xs) + cg * 16;
+    float* outp = a.out + (size_t)s * a.slab_stride;
+
+    auto finish_row = [&](int row, const VRaw (&v)[U], const IRaw (&o)[U]) {
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        spmm_consume<VT, CH, LPR, U>(xcol, tab, pitch, v, o, l, cps, acc);
+        if (cps > U * LPR) {   // long runs: further rounds, loaded and consumed in place
+            const VRaw* vrow; const IRaw* irow;
+            row_ptrs(row, vrow, irow);
+            for (int c0 = l + U * LPR; c0 - l < cps; c0 += U * LPR) {
+                VRaw vt[U];
+                IRaw ot[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int c = min(c0 + u * LPR, cps - 1);
+                    vt[u] = vrow[c];
+                    ot[u] = irow[c];
+                }
+                spmm_consume<VT, CH, LPR, U>(xcol, tab, pitch, vt, ot, c0, cps, acc);
+            }
+        }
+#pragma unroll
+        for (int n = 0; n < 4; ++n) acc[n] = group_sum<LPR>(acc[n]);
+        if (l == 0 && row < r_end) {
+            float* dst = outp + (size_t)row * a.ld_out + n0 + cg * 4;
+#pragma unroll
+            for (int n = 0; n < 4; ++n)
+                if (cg * 4 + n < ntw) dst[n] = acc[n];
+        }
+    };
+
+    // (4) row passes, two register sets: the next pass is in flight while this one
+    // is consumed.  All lanes of a (row, column group) share `r`, so they leave together.
+    for (; r < r_end; r += 2 * rows_per_pass) {
+        {
+            const VRaw* vrow; const IRaw* irow;
+            row_ptrs(r + rows_per_pass, vrow, irow);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = min(l + u * LPR, cps - 1);
+                vB[u] = vrow[c];
+                oB[u] = irow[c];
+            }
+        }
+        finish_row(r, vA, oA);
+        if (r + rows_per_pass >= r_end) break;
+        {
+            const VRaw* vrow; const IRaw* irow;
+            row_ptrs(r + 2 * rows_per_pass, vrow, irow);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = min(l + u * LPR, cps - 1);
+                vA[u] = vrow[c];
+                oA[u] = irow[c];
+            }
+        }
+        finish_row(r + rows_per_pass, vB, oB);
+    }
+}
+
+template <typename VT, int CH, int LPR, int U>
+int spmm_launch_one(const SpmmArgs& a, const SpmmLaunch& l) {
+    auto kern = spmm_kernel<VT, CH, LPR, U>;
+    if (l.lds > 48 * 1024) {
+        static bool raised = false;   // per instantiation; raising it twice is harmless
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               kMaxLdsBytes);
+            if (e != hipSuccess) return BS_ERR_HIP;
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3(a.wgs_per_xcd * kXcds), dim3(l.threads), l.lds, l.st, a);
+    return hip_status(hipGetLastError());
+}
+
+template <typename VT, int CH, int LPR>
+int spmm_launch_u(int u, const SpmmArgs& a, const SpmmLaunch& l) {
+    if (u == 2) return spmm_launch_one<VT, CH, LPR, 2>(a, l);
+    if (u == 4) return spmm_launch_one<VT, CH, LPR, 4>(a, l);
+    return BS_ERR_UNSUPPORTED;
+}
+
+template <typename VT, int CH>
+int spmm_launch_lpr(int lpr, int u, const SpmmArgs& a, const SpmmLaunch& l) {
+    switch (lpr) {
+        case 1: return spmm_launch_u<VT, CH, 1>(u, a, l);
+        case 2: return spmm_launch_u<VT, CH, 2>(u, a, l);
+        case 4: return spmm_launch_u<VT, CH, 4>(u, a, l);
+        case 8: return spmm_launch_u<VT, CH, 8>(u, a, l);
+        case 16: return spmm_launch_u<VT, CH, 16>(u, a, l);
+        case 32: return spmm_launch_u<VT, CH, 32>(u, a, l);
+        case 64: return spmm_launch_u<VT, CH, 64>(u, a, l);
+    }
+    return BS_ERR_UNSUPPORTED;
+}
+
+#endif  // __HIPCC__
+}  // namespace bs

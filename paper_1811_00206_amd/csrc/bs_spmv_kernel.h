@@ -63,22 +63,6 @@ int spmv_launch_f16(int ch, int lpr, int u, const SpmvArgs& a, const SpmvLaunch&
 
 #ifdef __HIPCC__
 
-// s_waitcnt: at most N vector-memory loads outstanding, no LDS/scalar operation
-// outstanding (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 left at
-// its maximum, lgkmcnt 11:8).
-template <int N>
-__device__ __forceinline__ void wait_vm_and_lds() {
-    static_assert(N >= 0 && N < 64, "vmcnt range");
-    __builtin_amdgcn_s_waitcnt((N & 0xf) | (0x7 << 4) | (0x0 << 8) | (((N >> 4) & 0x3) << 14));
-}
-
-// Nothing that touches memory moves across this point, neither in the
-// optimiser nor in the instruction scheduler.
-__device__ __forceinline__ void pin_order() {
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
-}
-
 // Sum over the U chunk slots a lane holds in registers.  Slot u is chunk
 // c0 + u*LPR of the row; slots past the end of the row hold a re-read of the
 // row's last chunk (valid memory) and are masked out here.  MODE as in

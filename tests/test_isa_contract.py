@@ -19,7 +19,7 @@ import pytest
 
 from paper_1811_00206_amd import build as bs_build
 
-SOURCES = ["bs_spmv_f32.hip", "bs_spmv_f16.hip"]
+SOURCES = ["bs_spmv_f32.hip", "bs_spmv_f16.hip", "bs_spmm_f32.hip", "bs_spmm_f16.hip"]
 
 
 def _assembly(src):
@@ -34,11 +34,12 @@ def _assembly(src):
 
 
 def _kernels(text):
-    """name -> list of instruction lines, for every spmv_kernel instantiation."""
+    """name -> list of instruction lines (plus the "; bs_pin" markers that
+    pin_order() leaves), for every spmv_kernel / spmm_kernel instantiation."""
     out = {}
     cur = None
     for line in text.splitlines():
-        m = re.match(r"^(_ZN2bs11spmv_kernel\w+):", line)
+        m = re.match(r"^(_ZN2bs11sp(?:mv|mm)_kernel\w+):", line)
         if m:
             cur = m.group(1)
             out[cur] = []
@@ -47,6 +48,8 @@ def _kernels(text):
             s = line.strip()
             if s.startswith("s_endpgm"):
                 cur = None
+            elif s.startswith("; bs_pin"):
+                out[cur].append("bs_pin")
             elif s and not s.startswith((";", ".")):
                 out[cur].append(s)
     return out
@@ -58,7 +61,7 @@ def _is_vmem_load(ins):
 
 @pytest.fixture(scope="module")
 def kernels():
-    with ThreadPoolExecutor(2) as ex:
+    with ThreadPoolExecutor(4) as ex:
         texts = list(ex.map(_assembly, SOURCES))
     ks = {}
     for t in texts:
@@ -67,8 +70,10 @@ def kernels():
 
 
 def test_every_instantiation_is_present(kernels):
-    # 3 chunk widths for fp32 + 4 for fp16, 7 group widths, 4 in-flight depths
-    assert len(kernels) == (3 + 4) * 7 * 4
+    # 3 chunk widths for fp32 + 4 for fp16, 7 group widths; 4 in-flight depths for
+    # SpMV, 2 for SpMM
+    assert sum("spmv_kernel" in n for n in kernels) == (3 + 4) * 7 * 4
+    assert sum("spmm_kernel" in n for n in kernels) == (3 + 4) * 7 * 2
 
 
 def test_wait_before_barrier_covers_the_copy_of_x(kernels):
@@ -76,18 +81,21 @@ def test_wait_before_barrier_covers_the_copy_of_x(kernels):
         barrier = next(i for i, s in enumerate(ins) if s.startswith("s_barrier"))
         dma = [i for i, s in enumerate(ins[:barrier]) if s.startswith("global_load_lds")]
         assert dma, f"{name}: no direct-to-LDS load before the barrier"
-        last_dma = dma[-1]
-        waits = [i for i in range(last_dma, barrier) if ins[i].startswith("s_waitcnt")
+        pins = [i for i, s in enumerate(ins[:barrier]) if s == "bs_pin"]
+        assert len(pins) >= 2, f"{name}: pin markers missing"
+        first, second = pins[-2], pins[-1]
+        # every copy of x is issued before the first pin, the weight loads sit between
+        # the pins, and the wait follows the second pin
+        assert dma[-1] < first, f"{name}: a direct-to-LDS load follows the first pin"
+        waits = [i for i in range(second, barrier) if ins[i].startswith("s_waitcnt")
                  and "vmcnt" in ins[i]]
-        assert waits, f"{name}: no vmcnt wait between the copy of x and the barrier"
-        w = waits[-1]
-        n_allowed = int(re.search(r"vmcnt\((\d+)\)", ins[w]).group(1))
-        issued_after = sum(_is_vmem_load(s) and not s.startswith("global_load_lds")
-                           for s in ins[last_dma + 1:w])
-        assert n_allowed <= issued_after, (
-            f"{name}: waits for vmcnt({n_allowed}) but only {issued_after} loads follow the "
-            "last direct-to-LDS load: x may not have landed at the barrier")
-        # nothing that reads LDS may sit between that wait and the barrier
-        assert not any(s.startswith("ds_read") for s in ins[w:barrier]), name
-        # and no LDS read of x before the barrier at all
+        assert waits, f"{name}: no vmcnt wait between the weight loads and the barrier"
+        n_allowed = int(re.search(r"vmcnt\((\d+)\)", ins[waits[-1]]).group(1))
+        issued = sum(_is_vmem_load(s) for s in ins[first:second])
+        assert n_allowed <= issued, (
+            f"{name}: waits for vmcnt({n_allowed}) but only {issued} loads sit between the "
+            "pins: x may not have landed at the barrier")
+        assert not any(_is_vmem_load(s) for s in ins[second:barrier]), (
+            f"{name}: a load between the second pin and the barrier would break the count")
+        # no LDS read before the barrier at all
         assert not any(s.startswith("ds_read") for s in ins[:barrier]), name
