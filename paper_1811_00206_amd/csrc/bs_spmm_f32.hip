@@ -2,11 +2,11 @@
 #include "bs_spmm_kernel.h"
 
 namespace bs {
-int spmm_launch_f32(int ch, int lpr, int u, const SpmmArgs& a, const SpmmLaunch& l) {
+int spmm_launch_f32(int ch, int lpr, int u, int q, const SpmmArgs& a, const SpmmLaunch& l) {
     switch (ch) {
-        case 4: return spmm_launch_lpr<float, 4>(lpr, u, a, l);
-        case 2: return spmm_launch_lpr<float, 2>(lpr, u, a, l);
-        case 1: return spmm_launch_lpr<float, 1>(lpr, u, a, l);
+        case 4: return spmm_launch_lpr<float, 4>(lpr, u, q, a, l);
+        case 2: return spmm_launch_lpr<float, 2>(lpr, u, q, a, l);
+        case 1: return spmm_launch_lpr<float, 1>(lpr, u, q, a, l);
     }
     return BS_ERR_UNSUPPORTED;
 }

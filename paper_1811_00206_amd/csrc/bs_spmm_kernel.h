@@ -11,9 +11,10 @@
 //     columns of X (sb*B rows of nl*4 floats) is copied into LDS with
 //     direct-to-LDS loads; a workgroup owns one tile and a range of rows;
 //   * within a wavefront LPR lanes share a (row, column group) and walk the
-//     row's entries of the slab in 16-byte value chunks, nl column groups of 4
-//     columns sit side by side, and the remaining lanes take further rows; an
-//     entry costs one 16-byte LDS read and four multiply-adds per lane;
+//     row's entries of the slab in 16-byte value chunks, nl column groups of
+//     4*Q columns sit side by side, and the remaining lanes take further rows;
+//     an entry costs one address computation, Q 16-byte LDS reads and 4*Q
+//     multiply-adds per lane;
 //   * the LDS address of an entry comes from a per-workgroup table
 //     (position in the slab -> byte offset of its bank's rows), as in SpMV;
 //   * the chunks of the next row pass are loaded while the current pass is
@@ -42,7 +43,7 @@ struct SpmmArgs {
     int nb;
     int sb, n_slabs;       // banks per slab
     int nt, n_tiles;       // columns per tile
-    int nl;                // column groups (of 4) per tile: 1, 2, 4, 8 or 16
+    int nl;                // column groups (of 4*Q columns) per tile: power of two, nl*LPR <= 64
     int rows_per_wg, row_groups;
     int total_wgs, wgs_per_xcd;
     int table_off;         // float index in LDS of the position table
@@ -56,18 +57,18 @@ struct SpmmLaunch {
     hipStream_t st;
 };
 
-int spmm_launch_f32(int ch, int lpr, int u, const SpmmArgs& a, const SpmmLaunch& l);
-int spmm_launch_f16(int ch, int lpr, int u, const SpmmArgs& a, const SpmmLaunch& l);
+int spmm_launch_f32(int ch, int lpr, int u, int q, const SpmmArgs& a, const SpmmLaunch& l);
+int spmm_launch_f16(int ch, int lpr, int u, int q, const SpmmArgs& a, const SpmmLaunch& l);
 
 #ifdef __HIPCC__
 
-// Four column sums over the U chunk slots a lane holds; slot u is chunk c0 + u*LPR
-// of the row's run inside the slab (`cps` chunks).  xcol points at the lane's 4
+// 4*Q column sums over the U chunk slots a lane holds; slot u is chunk c0 + u*LPR
+// of the row's run inside the slab (`cps` chunks).  xcol points at the lane's
 // columns of LDS row 0; pitch = bytes per LDS row.
-template <typename VT, int CH, int LPR, int U, typename VRaw, typename IRaw>
+template <typename VT, int CH, int LPR, int U, int Q, typename VRaw, typename IRaw>
 __device__ __forceinline__ void spmm_consume(const char* xcol, const uint32_t* tab, uint32_t pitch,
                                              const VRaw (&v)[U], const IRaw (&o)[U], int c0,
-                                             int cps, float (&acc)[4]) {
+                                             int cps, float (&acc)[4 * Q]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int c = c0 + u * LPR;
@@ -86,23 +87,30 @@ __device__ __forceinline__ void spmm_consume(const char* xcol, const uint32_t* t
         } else {
             base[0] = t[0];
         }
-        float p[4] = {0.f, 0.f, 0.f, 0.f};
+        // sums of this slot alone, so that a masked slot (which gathers real X values
+        // through a re-read chunk) can be dropped whole, whatever those values are
+        float p[4 * Q];
+#pragma unroll
+        for (int n = 0; n < 4 * Q; ++n) p[n] = 0.f;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const float w = value_at<VT>(v[u], i);
-            const float4 xv = *reinterpret_cast<const float4*>(
-                xcol + base[i] + __umul24(offset_at(o[u], i), pitch));
-            p[0] = fmaf(w, xv.x, p[0]);
-            p[1] = fmaf(w, xv.y, p[1]);
-            p[2] = fmaf(w, xv.z, p[2]);
-            p[3] = fmaf(w, xv.w, p[3]);
+            const char* row = xcol + base[i] + __umul24(offset_at(o[u], i), pitch);
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const float4 xv = *reinterpret_cast<const float4*>(row + q * 16);
+                p[4 * q + 0] = fmaf(w, xv.x, p[4 * q + 0]);
+                p[4 * q + 1] = fmaf(w, xv.y, p[4 * q + 1]);
+                p[4 * q + 2] = fmaf(w, xv.z, p[4 * q + 2]);
+                p[4 * q + 3] = fmaf(w, xv.w, p[4 * q + 3]);
+            }
         }
 #pragma unroll
-        for (int n = 0; n < 4; ++n) acc[n] += ok ? p[n] : 0.f;
+        for (int n = 0; n < 4 * Q; ++n) acc[n] += ok ? p[n] : 0.f;
     }
 }
 
-template <typename VT, int CH, int LPR, int U>
+template <typename VT, int CH, int LPR, int U, int Q>
 __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
     extern __shared__ __align__(16) float Xs[];
     using VRaw = typename RawBytes<CH * sizeof(VT)>::type;
@@ -122,7 +130,8 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
     const int n0 = z * a.nt;
     const int ntw = min(a.nt, a.N - n0);          // live columns of this tile
     const int nl = a.nl;
-    const uint32_t pitch = (uint32_t)nl * 16u;    // bytes per LDS row
+    const int f4_per_row = nl * Q;                // LDS row = nl groups of Q float4
+    const uint32_t pitch = (uint32_t)f4_per_row * 16u;   // bytes per LDS row
     const int slab_rows = banks * a.B;
     const int seg = banks * a.k;                  // entries of one row inside the slab
     const int cps = seg / CH;                     // exact by construction of the plan
@@ -137,13 +146,13 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
 
     // (1) the tile of X -> LDS
     const float* Xg = a.X + (size_t)j0 * a.B * a.ldx + n0;
-    const int total_f4 = slab_rows * nl;
+    const int total_f4 = slab_rows * f4_per_row;
     if (a.dma) {
         const int wave = tid >> 6, lane = tid & 63, n_waves = nthr >> 6;
         for (int p = wave; p * 64 < total_f4; p += n_waves) {
             const int i = p * 64 + lane;
             if (i < total_f4) {
-                const int r = i / nl, c4 = i - r * nl;
+                const int r = i / f4_per_row, c4 = i - r * f4_per_row;
                 // columns past the tile's live width are never read back as results
                 const float* src = Xg + (size_t)r * a.ldx + min(c4 * 4, max(ntw - 4, 0));
                 __builtin_amdgcn_global_load_lds(
@@ -153,7 +162,7 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
         }
     } else {
         for (int i = tid; i < total_f4; i += nthr) {
-            const int r = i / nl, c4 = i - r * nl;
+            const int r = i / f4_per_row, c4 = i - r * f4_per_row;
             const float* src = Xg + (size_t)r * a.ldx + c4 * 4;
             float4 t;
             t.x = c4 * 4 + 0 < ntw ? src[0] : 0.f;
@@ -198,12 +207,14 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
     __builtin_amdgcn_s_barrier();
     pin_order();
 
-    const char* xcol = reinterpret_cast<const char*>(Xs) + cg * 16;
+    const char* xcol = reinterpret_cast<const char*>(Xs) + cg * (Q * 16);
     float* outp = a.out + (size_t)s * a.slab_stride;
 
     auto finish_row = [&](int row, const VRaw (&v)[U], const IRaw (&o)[U]) {
-        float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        spmm_consume<VT, CH, LPR, U>(xcol, tab, pitch, v, o, l, cps, acc);
+        float acc[4 * Q];
+#pragma unroll
+        for (int n = 0; n < 4 * Q; ++n) acc[n] = 0.f;
+        spmm_consume<VT, CH, LPR, U, Q>(xcol, tab, pitch, v, o, l, cps, acc);
         if (cps > U * LPR) {   // long runs: further rounds, loaded and consumed in place
             const VRaw* vrow; const IRaw* irow;
             row_ptrs(row, vrow, irow);
@@ -216,23 +227,23 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
                     vt[u] = vrow[c];
                     ot[u] = irow[c];
                 }
-                spmm_consume<VT, CH, LPR, U>(xcol, tab, pitch, vt, ot, c0, cps, acc);
+                spmm_consume<VT, CH, LPR, U, Q>(xcol, tab, pitch, vt, ot, c0, cps, acc);
             }
         }
 #pragma unroll
-        for (int n = 0; n < 4; ++n) acc[n] = group_sum<LPR>(acc[n]);
+        for (int n = 0; n < 4 * Q; ++n) acc[n] = group_sum<LPR>(acc[n]);
         if (l == 0 && row < r_end) {
-            float* dst = outp + (size_t)row * a.ld_out + n0 + cg * 4;
+            float* dst = outp + (size_t)row * a.ld_out + n0 + cg * (4 * Q);
 #pragma unroll
-            for (int n = 0; n < 4; ++n)
-                if (cg * 4 + n < ntw) dst[n] = acc[n];
+            for (int n = 0; n < 4 * Q; ++n)
+                if (cg * (4 * Q) + n < ntw) dst[n] = acc[n];
         }
     };
 
     // (4) row passes, two register sets: the next pass is in flight while this one
     // is consumed.  All lanes of a (row, column group) share `r`, so they leave together.
     for (; r < r_end; r += 2 * rows_per_pass) {
-        {
+        if (r + rows_per_pass < r_end) {
             const VRaw* vrow; const IRaw* irow;
             row_ptrs(r + rows_per_pass, vrow, irow);
 #pragma unroll
@@ -244,7 +255,7 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
         }
         finish_row(r, vA, oA);
         if (r + rows_per_pass >= r_end) break;
-        {
+        if (r + 2 * rows_per_pass < r_end) {
             const VRaw* vrow; const IRaw* irow;
             row_ptrs(r + 2 * rows_per_pass, vrow, irow);
 #pragma unroll
@@ -258,9 +269,9 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
     }
 }
 
-template <typename VT, int CH, int LPR, int U>
+template <typename VT, int CH, int LPR, int U, int Q>
 int spmm_launch_one(const SpmmArgs& a, const SpmmLaunch& l) {
-    auto kern = spmm_kernel<VT, CH, LPR, U>;
+    auto kern = spmm_kernel<VT, CH, LPR, U, Q>;
     if (l.lds > 48 * 1024) {
         static bool raised = false;   // per instantiation; raising it twice is harmless
         if (!raised) {
@@ -275,23 +286,29 @@ int spmm_launch_one(const SpmmArgs& a, const SpmmLaunch& l) {
     return hip_status(hipGetLastError());
 }
 
+template <typename VT, int CH, int LPR, int U>
+int spmm_launch_q(int q, const SpmmArgs& a, const SpmmLaunch& l) {
+    if (q == 1) return spmm_launch_one<VT, CH, LPR, U, 1>(a, l);
+    if (q == 2) return spmm_launch_one<VT, CH, LPR, U, 2>(a, l);
+    if (q == 4) return spmm_launch_one<VT, CH, LPR, U, 4>(a, l);
+    return BS_ERR_UNSUPPORTED;
+}
+
 template <typename VT, int CH, int LPR>
-int spmm_launch_u(int u, const SpmmArgs& a, const SpmmLaunch& l) {
-    if (u == 2) return spmm_launch_one<VT, CH, LPR, 2>(a, l);
-    if (u == 4) return spmm_launch_one<VT, CH, LPR, 4>(a, l);
+int spmm_launch_u(int u, int q, const SpmmArgs& a, const SpmmLaunch& l) {
+    if (u == 2) return spmm_launch_q<VT, CH, LPR, 2>(q, a, l);
+    if (u == 4) return spmm_launch_q<VT, CH, LPR, 4>(q, a, l);
     return BS_ERR_UNSUPPORTED;
 }
 
 template <typename VT, int CH>
-int spmm_launch_lpr(int lpr, int u, const SpmmArgs& a, const SpmmLaunch& l) {
+int spmm_launch_lpr(int lpr, int u, int q, const SpmmArgs& a, const SpmmLaunch& l) {
     switch (lpr) {
-        case 1: return spmm_launch_u<VT, CH, 1>(u, a, l);
-        case 2: return spmm_launch_u<VT, CH, 2>(u, a, l);
-        case 4: return spmm_launch_u<VT, CH, 4>(u, a, l);
-        case 8: return spmm_launch_u<VT, CH, 8>(u, a, l);
-        case 16: return spmm_launch_u<VT, CH, 16>(u, a, l);
-        case 32: return spmm_launch_u<VT, CH, 32>(u, a, l);
-        case 64: return spmm_launch_u<VT, CH, 64>(u, a, l);
+        case 4: return spmm_launch_u<VT, CH, 4>(u, q, a, l);
+        case 8: return spmm_launch_u<VT, CH, 8>(u, q, a, l);
+        case 16: return spmm_launch_u<VT, CH, 16>(u, q, a, l);
+        case 32: return spmm_launch_u<VT, CH, 32>(u, q, a, l);
+        case 64: return spmm_launch_u<VT, CH, 64>(u, q, a, l);
     }
     return BS_ERR_UNSUPPORTED;
 }
