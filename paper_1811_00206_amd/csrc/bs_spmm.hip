@@ -68,10 +68,26 @@ SpmmPlan plan_for(int quads, int dtype, int64_t M, int64_t K, int bank, int k, i
     p.lds_bytes = tile_bytes + (size_t)sb * k * 4;
 
     const int64_t cps = sb * k / ch;
-    int lpr = 4;
-    while (lpr < kWave / nl && (cps + lpr - 1) / lpr > 4) lpr <<= 1;
+    // lanes per (row, column group): as few idle lane-slots as possible (slots past
+    // the end of the run are skipped only when they are empty for every lane); among
+    // equals the narrowest group that needs one round of 4 slots, else two rounds
+    int lpr = 0;
+    int64_t best_slots = 0;
+    auto better = [&](int cand, int64_t slots) {
+        if (lpr == 0) return true;
+        const int64_t w_new = slots * cand, w_old = best_slots * lpr;
+        if (w_new != w_old) return w_new < w_old;
+        const bool one_new = slots <= 4, one_old = best_slots <= 4;
+        if (one_new != one_old) return one_new;
+        return one_new ? cand < lpr : cand > lpr;
+    };
+    for (int cand = 4; cand <= kWave / nl; cand <<= 1) {
+        const int64_t slots = (cps + cand - 1) / cand;
+        if (slots > 8 && cand < kWave / nl) continue;
+        if (better(cand, slots)) { lpr = cand; best_slots = slots; }
+    }
     p.lpr = lpr;
-    p.u = (cps + lpr - 1) / lpr <= 2 ? 2 : 4;
+    p.u = best_slots <= 2 ? 2 : 4;
     const int max_threads = p.lds_bytes > 80 * 1024 ? 1024 : p.lds_bytes > 40 * 1024 ? 512 : 256;
 
     int wg_per_cu = (int)((size_t)kMaxLdsBytes / p.lds_bytes);

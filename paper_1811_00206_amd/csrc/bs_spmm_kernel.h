@@ -68,9 +68,12 @@ int spmm_launch_f16(int ch, int lpr, int u, int q, const SpmmArgs& a, const Spmm
 template <typename VT, int CH, int LPR, int U, int Q, typename VRaw, typename IRaw>
 __device__ __forceinline__ void spmm_consume(const char* xcol, const uint32_t* tab, uint32_t pitch,
                                              const VRaw (&v)[U], const IRaw (&o)[U], int c0,
-                                             int cps, float (&acc)[4 * Q]) {
+                                             int round_base, int cps, float (&acc)[4 * Q]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+        // round_base = c0 - l is the same for every lane: a slot that lies past the
+        // end of the run for all of them is skipped by a scalar branch
+        if (round_base + u * LPR >= cps) break;
         const int c = c0 + u * LPR;
         const bool ok = c < cps;
         const uint32_t* t = tab + (ok ? c : 0) * CH;
@@ -214,7 +217,7 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
         float acc[4 * Q];
 #pragma unroll
         for (int n = 0; n < 4 * Q; ++n) acc[n] = 0.f;
-        spmm_consume<VT, CH, LPR, U, Q>(xcol, tab, pitch, v, o, l, cps, acc);
+        spmm_consume<VT, CH, LPR, U, Q>(xcol, tab, pitch, v, o, l, 0, cps, acc);
         if (cps > U * LPR) {   // long runs: further rounds, loaded and consumed in place
             const VRaw* vrow; const IRaw* irow;
             row_ptrs(row, vrow, irow);
@@ -227,7 +230,7 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
                     vt[u] = vrow[c];
                     ot[u] = irow[c];
                 }
-                spmm_consume<VT, CH, LPR, U, Q>(xcol, tab, pitch, vt, ot, c0, cps, acc);
+                spmm_consume<VT, CH, LPR, U, Q>(xcol, tab, pitch, vt, ot, c0, c0 - l, cps, acc);
             }
         }
 #pragma unroll
@@ -288,9 +291,9 @@ int spmm_launch_one(const SpmmArgs& a, const SpmmLaunch& l) {
 
 template <typename VT, int CH, int LPR, int U>
 int spmm_launch_q(int q, const SpmmArgs& a, const SpmmLaunch& l) {
+    // wider lanes (Q = 2, 4) were measured equal or slower (more LDS bank conflicts)
+    // and are not instantiated
     if (q == 1) return spmm_launch_one<VT, CH, LPR, U, 1>(a, l);
-    if (q == 2) return spmm_launch_one<VT, CH, LPR, U, 2>(a, l);
-    if (q == 4) return spmm_launch_one<VT, CH, LPR, U, 4>(a, l);
     return BS_ERR_UNSUPPORTED;
 }
 

@@ -69,10 +69,14 @@ int spmv_launch_f16(int ch, int lpr, int u, const SpmvArgs& a, const SpmvLaunch&
 // SpmvArgs::bank_mode.  Straight-line code: no branch depends on a lane.
 template <typename VT, int CH, int LPR, int U, int MODE, typename VRaw, typename IRaw>
 __device__ __forceinline__ float consume(const SpmvArgs& a, const float* xs, const VRaw (&v)[U],
-                                         const IRaw (&o)[U], int c0, int cpr) {
+                                         const IRaw (&o)[U], int c0, int round_base, int cpr) {
     float part[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+        part[u] = 0.f;
+        // round_base = c0 - lane_in_row is the same for every lane: a slot past the end
+        // of the row for all of them is skipped by a scalar branch
+        if (round_base + u * LPR >= cpr) continue;
         const int c = c0 + u * LPR;
         const bool ok = c < cpr;
         // first entry of the chunk: which bank, and where inside it (entry 0 of the
@@ -116,11 +120,13 @@ __device__ __forceinline__ float consume(const SpmvArgs& a, const float* xs, con
 template <typename VT, int CH, int LPR, int U, typename VRaw, typename IRaw>
 __device__ __forceinline__ float consume_table(const float* xs, const uint32_t* tab,
                                                const VRaw (&v)[U], const IRaw (&o)[U], int c0,
-                                               int cpr) {
+                                               int round_base, int cpr) {
     float part[U];
     const char* xbytes = reinterpret_cast<const char*>(xs);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+        part[u] = 0.f;
+        if (round_base + u * LPR >= cpr) continue;   // empty for every lane: scalar branch
         const int c = c0 + u * LPR;
         const bool ok = c < cpr;
         const uint32_t* t = tab + (ok ? c : 0) * CH;
@@ -155,14 +161,14 @@ __device__ __forceinline__ float consume_table(const float* xs, const uint32_t* 
 template <typename VT, int CH, int LPR, int U, typename VRaw, typename IRaw>
 __device__ __forceinline__ float consume_any(const SpmvArgs& a, const float* xs,
                                              const VRaw (&v)[U], const IRaw (&o)[U], int c0,
-                                             int cpr) {
+                                             int round_base, int cpr) {
     // table_off and bank_mode are the same for every lane of the grid: scalar branches
     if (a.table_off > 0)
         return consume_table<VT, CH, LPR, U>(
-            xs, reinterpret_cast<const uint32_t*>(xs + a.table_off), v, o, c0, cpr);
-    if (a.bank_mode == 0) return consume<VT, CH, LPR, U, 0>(a, xs, v, o, c0, cpr);
-    if (a.bank_mode == 1) return consume<VT, CH, LPR, U, 1>(a, xs, v, o, c0, cpr);
-    return consume<VT, CH, LPR, U, 2>(a, xs, v, o, c0, cpr);
+            xs, reinterpret_cast<const uint32_t*>(xs + a.table_off), v, o, c0, round_base, cpr);
+    if (a.bank_mode == 0) return consume<VT, CH, LPR, U, 0>(a, xs, v, o, c0, round_base, cpr);
+    if (a.bank_mode == 1) return consume<VT, CH, LPR, U, 1>(a, xs, v, o, c0, round_base, cpr);
+    return consume<VT, CH, LPR, U, 2>(a, xs, v, o, c0, round_base, cpr);
 }
 
 // VT: storage type of vals; CH: entries per chunk (CH*sizeof(VT) <= 16, CH divides
@@ -234,7 +240,7 @@ __global__ __launch_bounds__(1024) void spmv_kernel(SpmvArgs a) {
     pin_order();
 
     // (4) gather-multiply-add, then further rounds for rows longer than LPR*U chunks
-    float acc = consume_any<VT, CH, LPR, U>(a, xs, v, o, lane_in_row, cpr);
+    float acc = consume_any<VT, CH, LPR, U>(a, xs, v, o, lane_in_row, 0, cpr);
     for (int c0 = lane_in_row + U * LPR; c0 - lane_in_row < cpr; c0 += U * LPR) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -242,7 +248,7 @@ __global__ __launch_bounds__(1024) void spmv_kernel(SpmvArgs a) {
             v[u] = vrow[c];
             o[u] = irow[c];
         }
-        acc += consume_any<VT, CH, LPR, U>(a, xs, v, o, c0, cpr);
+        acc += consume_any<VT, CH, LPR, U>(a, xs, v, o, c0, c0 - lane_in_row, cpr);
     }
 
     acc = group_sum<LPR>(acc);
