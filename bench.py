@@ -101,6 +101,70 @@ def region_us(torch, fn, n):
     return s.elapsed_time(e) * 1e3 / n
 
 
+OTHER_WORKLOADS = ("tiny", "sweep_k32", "sweep_k16", "sweep_k8", "sweep_k4", "sweep_k2",
+                   "lstm1500_n8", "lstm1500_n32", "lstm1500_n128", "fc6_b1", "fc6_b16",
+                   "bench16k_k32")
+
+
+def quick_measure(torch, np, bs, workloads, dev, name, launches=200):
+    """One workload, cold, `launches` graph-replayed launches: time per launch."""
+    wl, W, X = workloads.make(name)
+    Wd = torch.from_numpy(W).to(dev)
+    Xd = torch.from_numpy(np.ascontiguousarray(X)).to(dev)
+    vals, idx = bs.bs_prune_pack(Wd, wl.bank, wl.k)
+    alg = wl.spmv_bytes()
+    R = max(2, -(-2 * LLC_BYTES // alg) + 1)
+    copies = [(vals, idx)] + [(vals.clone(), idx.clone()) for _ in range(R - 1)]
+    spmm = wl.N > 1
+    Y = torch.empty((wl.M, wl.N) if spmm else (wl.M,), dtype=torch.float32, device=dev)
+    if spmm:
+        code = bs.BS_F16 if wl.dtype == "f16" else bs.BS_F32
+        ws = torch.empty(max(16, bs.bs_spmm_workspace_bytes(code, wl.M, wl.K, wl.bank, wl.k, wl.N)),
+                         dtype=torch.uint8, device=dev)
+
+    def launch_all():
+        if spmm:
+            for i in range(launches):
+                v, ix = copies[i % R]
+                bs.bs_spmm(v, ix, wl.bank, Xd, out=Y, workspace=ws)
+        else:
+            cs = [bs.PreparedSpmv(v, ix, wl.bank, Xd, Y) for v, ix in copies]
+            for i in range(launches):
+                cs[i % R]()
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        launch_all()                                  # warm-up outside any graph
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        launch_all()
+    g.replay()
+    torch.cuda.synchronize()
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record()
+    g.replay()
+    e.record()
+    torch.cuda.synchronize()
+    us = s.elapsed_time(e) * 1e3 / launches
+    res = {"us": round(us, 2), "GBps": round(alg / us / 1e3, 1),
+           "frac_of_8TBps": round(alg / us / 1e3 / HBM_PEAK_GBS, 3)}
+    if spmm:
+        res["TFLOPs"] = round(wl.flops() / us / 1e6, 2)
+    # dense baseline, cold as well
+    Rd = max(2, -(-2 * LLC_BYTES // wl.dense_bytes()) + 1)
+    Wc = [Wd] + [Wd.clone() for _ in range(min(Rd, 8) - 1)]
+    n_d = 10 if spmm else 50
+    fn = (lambda i: bs.bs_dense_gemm(Wc[i % len(Wc)], Xd, out=Y)) if spmm else \
+         (lambda i: bs.bs_dense_gemv(Wc[i % len(Wc)], Xd, out=Y))
+    for i in range(2):
+        fn(i)
+    d_us = region_us(torch, fn, n_d)
+    res["dense_us"] = round(d_us, 1)
+    res["speedup_vs_dense"] = round(d_us / us, 2)
+    return res
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -296,6 +360,19 @@ def main():
         extras["prune_pack_us"] = round(p_us, 1)
         extras["prune_pack_GBps"] = round(p_bytes / p_us / 1e3, 1)
         ev.close()
+
+        # the other configurations of the metric, same protocol (cold, graph of launches),
+        # fewer launches: {us per launch, GB/s of algorithmic bytes, dense baseline us}
+        if not args.warm and args.workload == "lstm1500":
+            del copies, calls
+            others = {}
+            for name in OTHER_WORKLOADS:
+                try:
+                    others[name] = quick_measure(torch, np, bs, workloads, dev, name)
+                except Exception as exc:             # never lose the headline line
+                    others[name] = {"error": str(exc)[:200]}
+                torch.cuda.empty_cache()
+            extras["other_workloads_cold"] = others
     out["extras"] = extras
 
     if not args.no_cpu:
