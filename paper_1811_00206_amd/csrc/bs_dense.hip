@@ -67,7 +67,8 @@ __global__ __launch_bounds__(256) void dense_gemv_kernel(const VT* __restrict__ 
     }
 }
 
-// ---- GEMM: 64 x BN output tile per workgroup, K in steps of 32 through LDS ---
+// ---- GEMM without matrix cores (rows not 16-byte aligned): 64 x BN output tile
+//      per workgroup, K in steps of 32 through LDS ------------------------------
 constexpr int BM = 64, BK = 32;
 
 template <typename VT, int BN>
@@ -135,6 +136,133 @@ __global__ __launch_bounds__(256) void dense_gemm_kernel(const VT* __restrict__ 
     }
 }
 
+
+// ---- GEMM on the matrix cores: Y = W . X, the dense baseline SpMM is compared with --
+// This one IS a dense contraction, so it uses MFMA (v_mfma_f32_32x32x2f32: fp32
+// inputs, fp32 accumulate; binary16 weights are widened first).  A workgroup of four
+// S wavefronts owns 32 rows x 32*CT columns; the wavefronts split K S ways (that is
+// what puts enough loads in flight: the matrices here have few rows) and add their
+// tiles through LDS at the end.  Per step of KS k a lane loads KS/2 consecutive
+// weights of its row (16-byte loads, 128 contiguous bytes for KS = 64) and the
+// wavefront stages KS rows of X in LDS; the loads of the next step are issued before
+// the current step is multiplied.
+// Operand layout of the instruction: lane l holds A[m = l%32][k = l/32] and
+// B[k = l/32][n = l%32]; accumulator register v of lane l is
+// D[m = 8*(v/4) + 4*(l/32) + v%4][n = l%32].
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+template <typename VT, int CT, int KS, int S>
+__global__ __launch_bounds__(64 * S) void dense_gemm_mfma(const VT* __restrict__ W,
+                                                       const float* __restrict__ X,
+                                                       float* __restrict__ Y, int M, int K, int N,
+                                                       int64_t ldx, int64_t ldy) {
+    constexpr int NT = 32 * CT;                    // columns per workgroup
+    constexpr int HK = KS / 2;                     // weights per lane and step
+    constexpr int E16 = 16 / sizeof(VT);           // weights per 16-byte load
+    constexpr int XR = KS * NT / kWave;            // X values a lane stages per step
+    extern __shared__ __align__(16) float smem[];  // Xs[S][KS][NT], later red[S-1][64][16*CT]
+    float (*Xs)[KS][NT] = reinterpret_cast<float (*)[KS][NT]>(smem);
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int r = lane & 31, h = lane >> 5;
+    const int row0 = blockIdx.x * 32, n0 = blockIdx.y * NT;
+    const int row = min(row0 + r, M - 1);
+    const int chunks = (K + KS - 1) / KS;
+    const int c_begin = wave * chunks / S, c_end = (wave + 1) * chunks / S;
+    const int steps = (chunks + S - 1) / S + 1;    // same trip count for all wavefronts
+
+    floatx16 acc[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[ct][v] = 0.f;
+
+    auto load_a = [&](int c, float (&a)[HK]) {
+        const int k = c * KS + HK * h;
+#pragma unroll
+        for (int q = 0; q < HK / E16; ++q) {
+            const int kq = k + q * E16;
+            if (c < c_end && kq < K) {             // K % E16 == 0: a 16-byte piece is all in or out
+                const uint4 raw = *reinterpret_cast<const uint4*>(W + (size_t)row * K + kq);
+                VT w[E16];
+                __builtin_memcpy(w, &raw, 16);
+#pragma unroll
+                for (int i = 0; i < E16; ++i) a[q * E16 + i] = to_f32<VT>(w[i]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < E16; ++i) a[q * E16 + i] = 0.f;
+            }
+        }
+    };
+    auto load_x = [&](int c, float (&x)[XR]) {
+#pragma unroll
+        for (int j = 0; j < XR; ++j) {
+            const int e = lane + j * kWave;
+            const int kk = c * KS + e / NT, n = n0 + e % NT;
+            x[j] = (c < c_end && kk < K && n < N) ? X[(size_t)kk * ldx + n] : 0.f;
+        }
+    };
+
+    float a_cur[HK], a_nxt[HK], x_nxt[XR];
+    load_a(c_begin, a_cur);
+    load_x(c_begin, x_nxt);
+    for (int t = 0; t < steps; ++t) {
+        // X rows of this step into LDS (all wavefronts make the same number of steps)
+#pragma unroll
+        for (int j = 0; j < XR; ++j) {
+            const int e = lane + j * kWave;
+            Xs[wave][e / NT][e % NT] = x_nxt[j];
+        }
+        __syncthreads();
+        load_a(c_begin + t + 1, a_nxt);
+        load_x(c_begin + t + 1, x_nxt);
+#pragma unroll
+        for (int i = 0; i < HK; ++i)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+                acc[ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                    a_cur[i], Xs[wave][HK * h + i][32 * ct + r], acc[ct], 0, 0, 0);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < HK; ++i) a_cur[i] = a_nxt[i];
+    }
+
+    // add the S shares of K (the X tiles are no longer needed: reuse their LDS), store
+    float (*red)[kWave][16 * CT] = reinterpret_cast<float (*)[kWave][16 * CT]>(smem);
+    if (wave > 0) {
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) red[wave - 1][lane][ct * 16 + v] = acc[ct][v];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float s = acc[ct][v];
+#pragma unroll
+                for (int w = 0; w < S - 1; ++w) s += red[w][lane][ct * 16 + v];
+                const int m = row0 + 8 * (v / 4) + 4 * h + (v % 4);
+                const int n = n0 + 32 * ct + r;
+                if (m < M && n < N) Y[(size_t)m * ldy + n] = s;
+            }
+    }
+}
+
+template <typename VT, int CT, int KS, int S>
+int gemm_mfma_launch(const VT* w, int64_t M, int64_t K, const float* X, int64_t N, int64_t ldx,
+                     float* Y, int64_t ldy, hipStream_t st) {
+    constexpr int NT = 32 * CT;
+    constexpr size_t lds =
+        sizeof(float) * (S * KS * NT > (S - 1) * 64 * 16 * CT ? S * KS * NT : (S - 1) * 64 * 16 * CT);
+    const dim3 grid((unsigned)((M + 31) / 32), (unsigned)((N + NT - 1) / NT));
+    hipLaunchKernelGGL((dense_gemm_mfma<VT, CT, KS, S>), grid, dim3(64 * S), lds, st, w, X, Y, (int)M,
+                       (int)K, (int)N, ldx, ldy);
+    return hip_status(hipGetLastError());
+}
+
 template <typename VT>
 int gemv_t(const void* W, int64_t M, int64_t K, const float* x, float* y, hipStream_t st) {
     constexpr int R = 2;
@@ -153,6 +281,10 @@ template <typename VT>
 int gemm_t(const void* W, int64_t M, int64_t K, const float* X, int64_t N, int64_t ldx, float* Y,
            int64_t ldy, hipStream_t st) {
     const VT* w = static_cast<const VT*>(W);
+    if (K % 8 == 0) {   // rows start on 16-byte boundaries: the matrix-core kernel
+        if (N <= 32) return gemm_mfma_launch<VT, 1, 16, 16>(w, M, K, X, N, ldx, Y, ldy, st);
+        return gemm_mfma_launch<VT, 2, 32, 8>(w, M, K, X, N, ldx, Y, ldy, st);
+    }
     const unsigned gm = (unsigned)((M + BM - 1) / BM);
     if (N <= 16) {
         dim3 g(gm, (unsigned)((N + 15) / 16));
