@@ -103,11 +103,14 @@ def region_us(torch, fn, n):
 
 OTHER_WORKLOADS = ("tiny", "sweep_k32", "sweep_k16", "sweep_k8", "sweep_k4", "sweep_k2",
                    "lstm1500_n8", "lstm1500_n32", "lstm1500_n128", "fc6_b1", "fc6_b16",
-                   "bench16k_k32")
+                   # Sec. 4.1's matrix shape, 50 % .. 97 % sparse, batch 1 and 8
+                   "bench16k_k128", "bench16k_k64", "bench16k_k32", "bench16k_k16", "bench16k_k8",
+                   "bench16k_k128_n8", "bench16k_k32_n8", "bench16k_k8_n8")
 
 
-def quick_measure(torch, np, bs, workloads, dev, name, launches=200):
-    """One workload, cold, `launches` graph-replayed launches: time per launch."""
+def quick_measure(torch, np, bs, workloads, dev, name, o_time, launches=200):
+    """One workload, cold, `launches` graph-replayed launches: time per launch.
+    o_time = measured launch floor, for eq. (5)'s ideal time."""
     wl, W, X = workloads.make(name)
     Wd = torch.from_numpy(W).to(dev)
     Xd = torch.from_numpy(np.ascontiguousarray(X)).to(dev)
@@ -162,6 +165,14 @@ def quick_measure(torch, np, bs, workloads, dev, name, launches=200):
     d_us = region_us(torch, fn, n_d)
     res["dense_us"] = round(d_us, 1)
     res["speedup_vs_dense"] = round(d_us / us, 2)
+    # eq. (5): the dense time scaled by the kept fraction, launch overhead not scaled
+    res["ideal_us_eq5"] = round(max(d_us - o_time, 0.0) * (1 - wl.sparsity) + o_time, 2)
+    # pruning + packing this matrix (W rotates as for the dense baseline)
+    pfn = lambda i: bs.bs_prune_pack(Wc[i % len(Wc)], wl.bank, wl.k)
+    pfn(0)
+    p_us = region_us(torch, pfn, 6)
+    res["prune_pack_us"] = round(p_us, 1)
+    res["prune_pack_GBps"] = round((W.nbytes + wl.nnz * (wl.val_bytes + 1)) / p_us / 1e3, 1)
     return res
 
 
@@ -368,7 +379,7 @@ def main():
             others = {}
             for name in OTHER_WORKLOADS:
                 try:
-                    others[name] = quick_measure(torch, np, bs, workloads, dev, name)
+                    others[name] = quick_measure(torch, np, bs, workloads, dev, name, o_time)
                 except Exception as exc:             # never lose the headline line
                     others[name] = {"error": str(exc)[:200]}
                 torch.cuda.empty_cache()

@@ -85,6 +85,8 @@ WORKLOADS = {w.name: w for w in [
     _mk(6, "bench16k_k32", 16384, 8192, 256, 32, 1.0),
     _mk(6, "bench16k_k16", 16384, 8192, 256, 16, 1.0),
     _mk(6, "bench16k_k8", 16384, 8192, 256, 8, 1.0),
+    _mk(6, "bench16k_k128_n8", 16384, 8192, 256, 128, 1.0, N=8),
+    _mk(6, "bench16k_k32_n8", 16384, 8192, 256, 32, 1.0, N=8),
     _mk(6, "bench16k_k8_n8", 16384, 8192, 256, 8, 1.0, N=8),
 ]}
 

@@ -181,6 +181,34 @@ def test_spmm_full_size(name):
     assert Y.tobytes() == Y2.tobytes()      # slab sums are added in a fixed order
 
 
+@pytest.mark.parametrize("name", ["bench16k_k128", "bench16k_k32", "bench16k_k8",
+                                  "bench16k_k32_n8", "bench16k_k8_n8"])
+def test_benchmark_shape_sampled_rows(name):
+    """Sec. 4.1's 16384 x 8192 matrix (32 banks of 256 per row) in the launch shape the
+    bench times: the GPU packs and multiplies the whole matrix, the oracle does the
+    rows of a spread sample one by one (the quadratic rank count over 134 M elements
+    would take minutes); rows are independent, so a row's result does not depend on
+    which other rows are present."""
+    say("benchmark shape", name)
+    wl, W, X = workloads.make(name)
+    rows = np.unique(np.concatenate([np.arange(0, wl.M, 257), [1, 63, 64, wl.M - 2, wl.M - 1]]))
+    Ws = np.ascontiguousarray(W[rows])
+    v_ref, i_ref = bs_ref.prune_pack(Ws, wl.bank, wl.k)
+    vals, idx = bs.bs_prune_pack(dev(W), wl.bank, wl.k)
+    rsel = torch.from_numpy(rows).to(vals.device)
+    assert host(vals[rsel]).tobytes() == v_ref.tobytes()
+    assert host(idx[rsel]).tobytes() == i_ref.tobytes()
+    if wl.N == 1:
+        y_ref = bs_ref.spmv(v_ref, i_ref, wl.bank, X)
+        y = host(bs.bs_spmv(vals, idx, wl.bank, dev(X)))[rows]
+    else:
+        y_ref = bs_ref.spmm(v_ref, i_ref, wl.bank, X)
+        y = host(bs.bs_spmm(vals, idx, wl.bank, dev(X)))[rows]
+    err = bs_ref.rel_l2(y, y_ref)
+    say("  relL2 on", len(rows), "rows", err)
+    assert err <= TOL[wl.dtype]
+
+
 def test_spmm_n1_matches_spmv_and_f16_small():
     wl, W, x = workloads.make("tiny")
     v, i = bs_ref.prune_pack(W, wl.bank, wl.k)
