@@ -313,6 +313,56 @@ int bs_ref_spmv(const void *vals, int is_f16, const uint8_t *idx, int64_t M,
     return bs_ref_spmm(vals, is_f16, idx, M, K, B, k, x, 1, 1, y, 1, threads);
 }
 
+/* ---------- one LSTM time step on a Balanced-Sparsity gate matrix ----------
+ *
+ * The paper's recurrent models (Sec. 4.3: a language model with 1500 hidden
+ * units, a bidirectional model with 1024) are LSTM cells whose four gate
+ * matrices are stacked into one 4H x (I + H) matrix; eq. (1) gives the layer
+ * as W.X + B.  The paper does not print the cell, so this is the textbook
+ * definition, with the gate blocks in the order input, forget, cell candidate,
+ * output (rows [0,H), [H,2H), [2H,3H), [3H,4H)):
+ *     a    = W_sparse . [x ; h_in] + bias
+ *     i, f, o = logistic(a_i), logistic(a_f), logistic(a_o);  g = tanh(a_g)
+ *     c_out = f * c_in + i * g
+ *     h_out = o * tanh(c_out)
+ * Everything in double (the products as in row_dot_f64), c_out and h_out
+ * rounded to float once; h_out uses the unrounded c_out.
+ */
+int bs_ref_lstm_step(const void *vals, int is_f16, const uint8_t *idx, int64_t H,
+                     int64_t I, int B, int k, const float *x, const float *h_in,
+                     const float *bias, const float *c_in, float *c_out, float *h_out)
+{
+    if (!vals || !idx || !x || !h_in || !bias || !c_in || !c_out || !h_out)
+        return BS_REF_ERR_NULL;
+    if (H < 1 || I < 1) return BS_REF_ERR_SHAPE;
+    int64_t K = I + H, M = 4 * H;
+    if (!shape_ok(M, K, B, k)) return BS_REF_ERR_SHAPE;
+    float *xh = (float *)malloc((size_t)K * sizeof(float));
+    if (!xh) return BS_REF_ERR_SHAPE;
+    memcpy(xh, x, (size_t)I * sizeof(float));
+    memcpy(xh + I, h_in, (size_t)H * sizeof(float));
+    int st = BS_REF_OK;
+    for (int64_t u = 0; u < H && !st; ++u) {
+        double a[4];
+        for (int g = 0; g < 4 && !st; ++g) {
+            st = row_dot_f64(vals, is_f16, idx, K, B, k, xh, 1, g * H + u, 0, &a[g]);
+            if (!isfinite((double)bias[g * H + u])) st = BS_REF_ERR_NONFINITE;
+            a[g] += (double)bias[g * H + u];
+        }
+        if (st) break;
+        if (!isfinite((double)c_in[u])) { st = BS_REF_ERR_NONFINITE; break; }
+        double gi = 1.0 / (1.0 + exp(-a[0]));
+        double gf = 1.0 / (1.0 + exp(-a[1]));
+        double gg = tanh(a[2]);
+        double go = 1.0 / (1.0 + exp(-a[3]));
+        double c = gf * (double)c_in[u] + gi * gg;
+        c_out[u] = (float)c;
+        h_out[u] = (float)(go * tanh(c));
+    }
+    free(xh);
+    return st;
+}
+
 /* ---------- dense product, all K columns in ascending order, double ------ */
 
 /* Yd = Wd . X with Wd a dense M x K matrix (fp32 or binary16 bits) */

@@ -55,6 +55,7 @@ def _load():
         lib.bs_ref_spmm.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, i64, i64, vp, i64, i32]
         lib.bs_ref_spmv.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, vp, i32]
         lib.bs_ref_dense_gemm_f64.argtypes = [vp, i32, i64, i64, vp, i64, i64, vp, i64]
+        lib.bs_ref_lstm_step.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp]
         lib.bs_ref_rel_l2.argtypes = [vp, vp, i64]
         lib.bs_ref_rel_l2.restype = ctypes.c_double
         _lib = lib
@@ -165,6 +166,41 @@ def spmv(vals, idx, bank: int, x, threads: int = 1) -> np.ndarray:
     if st:
         raise OracleError(st, "spmv")
     return y
+
+
+def lstm_step(vals, idx, bank: int, x, h, bias, c):
+    """One LSTM step on the packed 4H x (I+H) gate matrix (gate blocks i, f, g, o):
+    returns (c_out, h_out) as fp32."""
+    is16, vals = _storage(vals, "vals")
+    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    M, nb, k = vals.shape
+    H = M // 4
+    K = nb * bank
+    I = K - H
+    if M != 4 * H or I < 1:
+        raise ValueError("gate matrix must be 4H x (I + H)")
+    f32 = lambda a, n: np.ascontiguousarray(a, dtype=np.float32).reshape(n)
+    x, h, bias, c = f32(x, I), f32(h, H), f32(bias, 4 * H), f32(c, H)
+    c_out = np.empty(H, dtype=np.float32)
+    h_out = np.empty(H, dtype=np.float32)
+    st = _load().bs_ref_lstm_step(_p(vals), is16, _p(idx), H, I, bank, k, _p(x), _p(h), _p(bias),
+                                  _p(c), _p(c_out), _p(h_out))
+    if st:
+        raise OracleError(st, "lstm_step")
+    return c_out, h_out
+
+
+def lstm_sequence(vals, idx, bank: int, X, h0, bias, c0):
+    """T steps, X is [T, I]; the state is carried in fp32 between steps.  Returns
+    (H_all [T, H], c_T)."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    h = np.asarray(h0, dtype=np.float32)
+    c = np.asarray(c0, dtype=np.float32)
+    out = np.empty((X.shape[0], h.size), dtype=np.float32)
+    for t in range(X.shape[0]):
+        c, h = lstm_step(vals, idx, bank, X[t], h, bias, c)
+        out[t] = h
+    return out, c
 
 
 def dense_gemm_f64(Wd: np.ndarray, X) -> np.ndarray:

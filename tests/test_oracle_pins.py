@@ -324,3 +324,91 @@ def test_rel_l2():
     a = np.array([3.0, 4.5], dtype=np.float32)
     assert bs_ref.rel_l2(a, b) == pytest.approx(0.1)
     assert bs_ref.rel_l2(b, b) == 0.0
+
+
+# ------------------------------------------------------ LSTM step (Sec. 4.3 models)
+
+def lstm_inputs(H, I, bank, k, seed, sigma=0.3, dtype=np.float32):
+    W = rand_w(4 * H, I + H, seed, dtype=dtype, sigma=sigma)
+    vals, idx = bs_ref.prune_pack(W, bank, k)
+    rng = np.random.Generator(np.random.PCG64(seed + 1))
+    x = rng.uniform(-1, 1, I).astype(np.float32)
+    h = rng.uniform(-1, 1, H).astype(np.float32)
+    c = rng.uniform(-2, 2, H).astype(np.float32)
+    bias = rng.uniform(-1, 1, 4 * H).astype(np.float32)
+    return vals, idx, x, h, c, bias
+
+
+@pytest.mark.parametrize("H,I,bank,k", [(8, 24, 16, 3), (12, 20, 8, 8), (5, 11, 4, 1)])
+def test_lstm_step_against_library_cell(H, I, bank, k):
+    """torch.nn.LSTMCell (its own code, gate blocks i, f, g, o, input and recurrent
+    weights held apart) on the unpacked matrix in float64: pins the gate order, the
+    split of the columns into x and h, every sign and both nonlinearities."""
+    import torch
+    vals, idx, x, h, c, bias = lstm_inputs(H, I, bank, k, 31)
+    Wp = bs_ref.unpack(vals, idx, bank).astype(np.float64)
+    cell = torch.nn.LSTMCell(I, H, bias=True, dtype=torch.float64)
+    with torch.no_grad():
+        cell.weight_ih.copy_(torch.from_numpy(Wp[:, :I]))
+        cell.weight_hh.copy_(torch.from_numpy(Wp[:, I:]))
+        cell.bias_ih.copy_(torch.from_numpy(bias.astype(np.float64)))
+        cell.bias_hh.zero_()
+        h_t, c_t = cell(torch.from_numpy(x.astype(np.float64))[None],
+                        (torch.from_numpy(h.astype(np.float64))[None],
+                         torch.from_numpy(c.astype(np.float64))[None]))
+    c_out, h_out = bs_ref.lstm_step(vals, idx, bank, x, h, bias, c)
+    np.testing.assert_allclose(c_out, c_t[0].numpy(), rtol=2e-7, atol=1e-7)
+    np.testing.assert_allclose(h_out, h_t[0].numpy(), rtol=2e-7, atol=1e-7)
+
+
+def test_lstm_step_closed_forms():
+    H, I, bank, k = 6, 10, 8, 2
+    vals, idx, x, h, c, _ = lstm_inputs(H, I, bank, k, 32)
+    zero_v = np.zeros_like(vals)
+    # no weights, no bias: every logistic gate is 1/2 and the candidate is 0
+    c1, h1 = bs_ref.lstm_step(zero_v, idx, bank, x, h, np.zeros(4 * H, np.float32), c)
+    np.testing.assert_allclose(c1, 0.5 * c.astype(np.float64), rtol=1e-7)
+    np.testing.assert_allclose(h1, 0.5 * np.tanh(0.5 * c.astype(np.float64)), rtol=1e-7)
+    # forget gate pinned open, input gate pinned shut: the cell state passes through
+    b = np.zeros(4 * H, np.float32)
+    b[0:H] = -80.0
+    b[H:2 * H] = 80.0
+    c2, h2 = bs_ref.lstm_step(vals, idx, bank, x, h, b, c)
+    assert c2.tobytes() == c.tobytes()
+    # each gate block on its own, from hand-picked pre-activations:
+    # logistic(ln 3) = 3/4, tanh(atanh(1/2)) = 1/2, logistic(-ln 3) = 1/4
+    b = np.zeros(4 * H, np.float64)
+    b[0:H] = np.log(3.0)
+    b[H:2 * H] = -np.log(3.0)
+    b[2 * H:3 * H] = np.arctanh(0.5)
+    b[3 * H:] = np.log(3.0)
+    c3, h3 = bs_ref.lstm_step(zero_v, idx, bank, x, h, b.astype(np.float32), np.ones(H, np.float32))
+    np.testing.assert_allclose(c3, 0.25 * 1.0 + 0.75 * 0.5, rtol=1e-6)
+    np.testing.assert_allclose(h3, 0.75 * np.tanh(0.625), rtol=1e-6)
+
+
+def test_lstm_step_uses_the_sparse_product():
+    """Pre-activations are the sparse product of the stacked vector [x ; h]: with the
+    nonlinear part undone (tiny weights keep every gate in its linear range) the
+    cell candidate reads back W_sparse . [x ; h]."""
+    H, I, bank, k = 4, 12, 8, 3
+    vals, idx, x, h, c, _ = lstm_inputs(H, I, bank, k, 33, sigma=1e-3)
+    b = np.zeros(4 * H, np.float32)
+    b[0:H] = 80.0          # input gate open
+    b[H:2 * H] = -80.0     # forget gate shut: c_out = tanh(a_g)
+    c_out, _ = bs_ref.lstm_step(vals, idx, bank, x, h, b, c)
+    a = bs_ref.spmm_f64(vals, idx, bank, np.concatenate([x, h]))
+    np.testing.assert_allclose(np.arctanh(c_out.astype(np.float64)), a[2 * H:3 * H], rtol=1e-4,
+                               atol=1e-9)
+
+
+def test_lstm_sequence_is_the_step_repeated():
+    H, I, bank, k = 8, 8, 16, 4
+    vals, idx, x, h, c, bias = lstm_inputs(H, I, bank, k, 34)
+    X = np.stack([x, -x, 0.5 * x]).astype(np.float32)
+    Hs, cT = bs_ref.lstm_sequence(vals, idx, bank, X, h, bias, c)
+    c1, h1 = bs_ref.lstm_step(vals, idx, bank, X[0], h, bias, c)
+    c2, h2 = bs_ref.lstm_step(vals, idx, bank, X[1], h1, bias, c1)
+    c3, h3 = bs_ref.lstm_step(vals, idx, bank, X[2], h2, bias, c2)
+    assert Hs[0].tobytes() == h1.tobytes() and Hs[1].tobytes() == h2.tobytes()
+    assert Hs[2].tobytes() == h3.tobytes() and cT.tobytes() == c3.tobytes()
