@@ -372,6 +372,38 @@ def main():
         extras["prune_pack_GBps"] = round(p_bytes / p_us / 1e3, 1)
         ev.close()
 
+        # fused LSTM time steps (Sec. 4.3's language model: H = I = 1500 is this very gate
+        # matrix): T dependent steps replayed from one graph, weights cache resident as in
+        # a real recurrence; per step = the sparse product + bias, gates and cell update
+        if not spmm and wl.M % 4 == 0 and wl.K > wl.M // 4:
+            try:
+                Hn, T = wl.M // 4, 64
+                In = wl.K - Hn
+                Xs_h, h0_h, c0_h, b_h = workloads.draw_lstm_inputs(Hn, In, T, wl.seed)
+                Xs, h0, c0, bias = (torch.from_numpy(t).to(dev) for t in (Xs_h, h0_h, c0_h, b_h))
+                H_all = torch.empty((T, Hn), dtype=torch.float32, device=dev)
+                side = torch.cuda.Stream()
+                with torch.cuda.stream(side):
+                    bs.bs_lstm_sequence(vals, idx, wl.bank, Xs, h0, bias, c0, H_all=H_all)
+                torch.cuda.synchronize()
+                gl = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gl):
+                    bs.bs_lstm_sequence(vals, idx, wl.bank, Xs, h0, bias, c0, H_all=H_all)
+                gl.replay()
+                torch.cuda.synchronize()
+                s2, e2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                s2.record()
+                for _ in range(10):
+                    gl.replay()
+                e2.record()
+                torch.cuda.synchronize()
+                l_us = s2.elapsed_time(e2) * 1e3 / (10 * T)
+                extras["lstm_step_us_cache_resident"] = round(l_us, 3)
+                extras["lstm_steps_per_graph"] = T
+                extras["lstm_step_vs_dense_gemv_us"] = round(d_us, 2)
+            except Exception as exc:             # never lose the headline line
+                extras["lstm_error"] = str(exc)[:200]
+
         # the other configurations of the metric, same protocol (cold, graph of launches),
         # fewer launches: {us per launch, GB/s of algorithmic bytes, dense baseline us}
         if not args.warm and args.workload == "lstm1500":

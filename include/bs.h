@@ -120,6 +120,41 @@ int bs_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t 
             int bank, int k, const float* X, int64_t N, int64_t ldx,
             float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- one LSTM time step on a Balanced-Sparsity gate matrix (the recurrent
+ *      models of Sec. 4.3: hidden size 1500 / 1024; eq. (1): W.X + B) --------
+ *
+ * The packed matrix is the stacked gate matrix, 4H rows x (I + H) columns, gate
+ * blocks in the order input, forget, cell candidate, output (rows [0,H), [H,2H),
+ * [2H,3H), [3H,4H)); columns [0,I) multiply x, columns [I,I+H) multiply h_in.
+ * One kernel does the sparse product and the cell update:
+ *     a = W_sparse . [x ; h_in] + bias
+ *     c_out = logistic(a_f) * c_in + logistic(a_i) * tanh(a_g)
+ *     h_out = logistic(a_o) * tanh(c_out)
+ * vals, idx  DEVICE in   packed 4H x (I+H) matrix (bs_prune_pack of the stacked matrix)
+ * x          DEVICE in   I fp32          h_in  DEVICE in   H fp32
+ * bias       DEVICE in   4H fp32         c_in  DEVICE in   H fp32
+ * c_out      DEVICE out  H fp32 (may be the same buffer as c_in)
+ * h_out      DEVICE out  H fp32 (must not overlap h_in: BS_ERR_UNSUPPORTED if equal)
+ * Requires I % 4 == 0 and H % 4 == 0 (BS_ERR_UNSUPPORTED otherwise) and the
+ * shape rules above with M = 4H, K = I + H.  fp32 arithmetic throughout.
+ */
+int bs_lstm_step(const void* vals, const uint8_t* idx, int dtype, int64_t H, int64_t I,
+                 int bank, int k, const float* x, const float* h_in, const float* bias,
+                 const float* c_in, float* c_out, float* h_out, void* stream);
+
+/*
+ * T steps in a row, enqueued back to back on `stream` (one kernel per step; the
+ * packed matrix stays in the last-level cache between them):
+ * X      DEVICE in      T x I fp32, row t is the input of step t
+ * h0     DEVICE in      H fp32, the hidden state before step 0
+ * c      DEVICE in/out  H fp32: the cell state before step 0, after step T-1 on return
+ * H_all  DEVICE out     T x H fp32, row t is the hidden state after step t
+ *                       (must not overlap h0)
+ */
+int bs_lstm_sequence(const void* vals, const uint8_t* idx, int dtype, int64_t H, int64_t I,
+                     int bank, int k, const float* X, int64_t T, const float* h0,
+                     const float* bias, float* c, float* H_all, void* stream);
+
 /* ---- dense baseline the sparse path is compared with (Sec. 4: the paper's
  *      dense column; here a hand-written kernel on the same GPU) ----------- */
 

@@ -21,6 +21,7 @@ BS_F32, BS_F16 = 0, 1
 EXPORTS = (
     "bs_nnz", "bs_vals_bytes", "bs_idx_bytes", "bs_status_str", "bs_prune_pack", "bs_spmv",
     "bs_spmv_ex", "bs_spmm_workspace_bytes", "bs_spmm", "bs_dense_gemv", "bs_dense_gemm",
+    "bs_lstm_step", "bs_lstm_sequence",
 )
 
 
@@ -64,8 +65,10 @@ def load_library():
     lib.bs_spmm.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, i64, vp, i64, vp, sz, vp]
     lib.bs_dense_gemv.argtypes = [vp, i32, i64, i64, vp, vp, vp]
     lib.bs_dense_gemm.argtypes = [vp, i32, i64, i64, vp, i64, i64, vp, i64, vp]
+    lib.bs_lstm_step.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.bs_lstm_sequence.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, vp, vp, vp, vp, vp]
     for name in ("bs_prune_pack", "bs_spmv", "bs_spmv_ex", "bs_spmm", "bs_dense_gemv",
-                 "bs_dense_gemm"):
+                 "bs_dense_gemm", "bs_lstm_step", "bs_lstm_sequence"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -259,3 +262,50 @@ def bs_dense_gemm(W, X, out=None):
     _check(load_library().bs_dense_gemm(_ptr(W), code, M, K, _ptr(X), N, N, _ptr(Y), N, _stream()),
            "bs_dense_gemm")
     return Y
+
+
+def _lstm_shape(vals, idx, bank):
+    code, M, K, k = _packed(vals, idx, bank)
+    if M % 4:
+        raise ValueError("the gate matrix must have 4H rows")
+    H = M // 4
+    I = K - H
+    if I < 1:
+        raise ValueError("the gate matrix must have I + H columns with I >= 1")
+    return code, H, I, k
+
+
+def bs_lstm_step(vals, idx, bank: int, x, h, bias, c, c_out=None, h_out=None):
+    """One LSTM step on the packed 4H x (I+H) gate matrix: returns (c_out, h_out)."""
+    code, H, I, k = _lstm_shape(vals, idx, bank)
+    for t, name, n in ((x, "x", I), (h, "h", H), (bias, "bias", 4 * H), (c, "c", H)):
+        _dev(t, name, torch.float32)
+        if t.numel() != n:
+            raise ValueError(f"{name} must have {n} elements")
+    c_out = torch.empty(H, dtype=torch.float32, device=vals.device) if c_out is None else _dev(
+        c_out, "c_out", torch.float32)
+    h_out = torch.empty(H, dtype=torch.float32, device=vals.device) if h_out is None else _dev(
+        h_out, "h_out", torch.float32)
+    _check(load_library().bs_lstm_step(_ptr(vals), _ptr(idx), code, H, I, bank, k, _ptr(x), _ptr(h),
+                                       _ptr(bias), _ptr(c), _ptr(c_out), _ptr(h_out), _stream()),
+           "bs_lstm_step")
+    return c_out, h_out
+
+
+def bs_lstm_sequence(vals, idx, bank: int, X, h0, bias, c, H_all=None):
+    """T steps; X is [T, I]; `c` is updated in place.  Returns H_all [T, H]."""
+    code, H, I, k = _lstm_shape(vals, idx, bank)
+    _dev(X, "X", torch.float32)
+    if X.dim() != 2 or X.shape[1] != I:
+        raise ValueError(f"X must be [T, {I}]")
+    T = X.shape[0]
+    for t, name, n in ((h0, "h0", H), (bias, "bias", 4 * H), (c, "c", H)):
+        _dev(t, name, torch.float32)
+        if t.numel() != n:
+            raise ValueError(f"{name} must have {n} elements")
+    H_all = torch.empty((T, H), dtype=torch.float32, device=vals.device) if H_all is None else _dev(
+        H_all, "H_all", torch.float32)
+    _check(load_library().bs_lstm_sequence(_ptr(vals), _ptr(idx), code, H, I, bank, k, _ptr(X), T,
+                                           _ptr(h0), _ptr(bias), _ptr(c), _ptr(H_all), _stream()),
+           "bs_lstm_sequence")
+    return H_all

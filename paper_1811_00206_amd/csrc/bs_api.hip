@@ -84,6 +84,37 @@ int bs_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t 
     return bs_spmv_ex(vals, idx, dtype, M, K, bank, k, x, y, 0, 0, nullptr, nullptr, stream);
 }
 
+int bs_lstm_step(const void* vals, const uint8_t* idx, int dtype, int64_t H, int64_t I, int bank,
+                 int k, const float* x, const float* h_in, const float* bias, const float* c_in,
+                 float* c_out, float* h_out, void* stream) {
+    if (!x || !h_in || !bias || !c_in || !c_out || !h_out) return BS_ERR_NULL;
+    if (H < 1 || I < 1 || H > (INT64_MAX >> 3) || I > (INT64_MAX >> 3)) return BS_ERR_SHAPE;
+    int st = check_packed(vals, idx, dtype, 4 * H, I + H, bank, k);
+    if (st) return st;
+    if (!aligned16(x) || !aligned16(h_in) || !aligned16(bias) || !aligned16(c_in) ||
+        !aligned16(c_out) || !aligned16(h_out))
+        return BS_ERR_ALIGN;
+    if (h_out == h_in) return BS_ERR_UNSUPPORTED;
+    return bs::launch_lstm_step(vals, idx, dtype, H, I, bank, k, x, h_in, bias, c_in, c_out, h_out,
+                                static_cast<hipStream_t>(stream));
+}
+
+int bs_lstm_sequence(const void* vals, const uint8_t* idx, int dtype, int64_t H, int64_t I,
+                     int bank, int k, const float* X, int64_t T, const float* h0,
+                     const float* bias, float* c, float* H_all, void* stream) {
+    if (!X || !h0 || !bias || !c || !H_all) return BS_ERR_NULL;
+    if (T < 1) return BS_ERR_SHAPE;
+    if (H_all == h0) return BS_ERR_UNSUPPORTED;
+    // rows of X and H_all start on 16-byte boundaries because I and H are multiples of 4
+    for (int64_t t = 0; t < T; ++t) {
+        const float* h_in = t == 0 ? h0 : H_all + (t - 1) * H;
+        int st = bs_lstm_step(vals, idx, dtype, H, I, bank, k, X + t * I, h_in, bias, c, c,
+                              H_all + t * H, stream);
+        if (st) return st;   // step 0 validates everything the later steps use
+    }
+    return BS_OK;
+}
+
 size_t bs_spmm_workspace_bytes(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N) {
     if (!shape_ok(M, K, bank, k) || !dtype_ok(dtype) || !size_ok(M, K, bank) || N < 1) return 0;
     return bs::spmm_workspace_bytes(dtype, M, K, bank, k, N);

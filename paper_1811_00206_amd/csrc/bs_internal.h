@@ -21,6 +21,10 @@ int launch_prune_pack(const void* W, int dtype, int64_t M, int64_t K, int bank, 
 int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
                 int k, const float* x, float* y, int lanes_per_row, int rows_per_wg,
                 hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st);
+// fused LSTM step: the matrix is 4H x (I + H); see bs_lstm_step in bs.h
+int launch_lstm_step(const void* vals, const uint8_t* idx, int dtype, int64_t H, int64_t I, int bank,
+                     int k, const float* x, const float* h_in, const float* bias,
+                     const float* c_in, float* c_out, float* h_out, hipStream_t st);
 size_t spmm_workspace_bytes(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N);
 int launch_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
                 int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,

@@ -3,9 +3,22 @@
 
 namespace bs {
 
-int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
-                int k, const float* x, float* y, int lanes_per_row, int rows_per_wg,
-                hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st) {
+namespace {
+
+struct LstmPart {
+    const float* h_in;
+    const float* bias;
+    const float* c_in;
+    float* c_out;
+    float* h_out;
+    int H, I;
+};
+
+// Shared by bs_spmv and the fused LSTM step (lstm != nullptr: M = 4H, K = I + H,
+// x is the first I entries of the input vector, y is unused).
+int launch_common(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                  int k, const float* x, float* y, int lanes_per_row, int rows_per_wg,
+                  const LstmPart* lstm, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st) {
     const int64_t row_len = (K / bank) * k;
     // LDS: x, then (if it fits) one word per row entry for the bank table
     const size_t x_floats = ((size_t)K + 3) / 4 * 4;
@@ -30,7 +43,7 @@ int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int6
         // smallest group that leaves at most 4 chunks per lane (measured best on both
         // the 9 MB and the 84 MB matrices: a short dependent chain per lane, still
         // 80 bytes in flight per lane); rows longer than 256 chunks use all 64 lanes
-        lpr = 1;
+        lpr = lstm ? 8 : 1;   // the fused step is built for 8..64 lanes per row
         while (lpr < 64 && (cpr + lpr - 1) / lpr > 4) lpr <<= 1;
     }
     if (lpr < 1 || lpr > 64 || (lpr & (lpr - 1))) return BS_ERR_UNSUPPORTED;
@@ -38,6 +51,7 @@ int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int6
     int64_t need = (cpr + lpr - 1) / lpr;
     int u = need >= kMaxInFlight ? kMaxInFlight : (int)((need + 1) / 2 * 2);
     if (u < 2) u = 2;
+    if (lstm) u = u <= 4 ? 4 : 8;
 
     int rpw = rows_per_wg;
     if (rpw == 0) {
@@ -47,6 +61,13 @@ int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int6
     }
     const int64_t threads = (int64_t)lpr * rpw;
     if (rpw < 1 || threads > 1024 || threads % kWave) return BS_ERR_UNSUPPORTED;
+    if (lstm && rpw % 4) return BS_ERR_UNSUPPORTED;   // whole units per workgroup
+    int pre_off = 0;
+    if (lstm) {   // the workgroup's pre-activations, behind x and the table
+        pre_off = (int)(lds / sizeof(float));
+        lds += (size_t)rpw * sizeof(float);
+        if (lds > (size_t)kMaxLdsBytes) return BS_ERR_UNSUPPORTED;
+    }
     const int64_t grid = (M + rpw - 1) / rpw;
     if (grid > INT32_MAX) return BS_ERR_UNSUPPORTED;
 
@@ -59,10 +80,34 @@ int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int6
     a.rows_per_wg = rpw;
     a.bank_mode = (k % ch == 0) ? 0 : (k >= ch ? 1 : 2);
     a.table_off = table_off;
+    a.h_in = nullptr; a.bias = nullptr; a.c_in = nullptr; a.c_out = nullptr; a.h_out = nullptr;
+    a.H = 0; a.I = 0; a.pre_off = pre_off;
+    if (lstm) {
+        a.h_in = lstm->h_in; a.bias = lstm->bias; a.c_in = lstm->c_in;
+        a.c_out = lstm->c_out; a.h_out = lstm->h_out; a.H = lstm->H; a.I = lstm->I;
+    }
 
-    const SpmvLaunch l{(int)threads, (int)grid, lds, ev_start, ev_stop, st};
+    const SpmvLaunch l{lstm != nullptr, (int)threads, (int)grid, lds, ev_start, ev_stop, st};
     if (dtype == BS_F16) return spmv_launch_f16(ch, lpr, u, a, l);
     return spmv_launch_f32(ch, lpr, u, a, l);
+}
+
+}  // namespace
+
+int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                int k, const float* x, float* y, int lanes_per_row, int rows_per_wg,
+                hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st) {
+    return launch_common(vals, idx, dtype, M, K, bank, k, x, y, lanes_per_row, rows_per_wg,
+                         nullptr, ev_start, ev_stop, st);
+}
+
+int launch_lstm_step(const void* vals, const uint8_t* idx, int dtype, int64_t H, int64_t I, int bank,
+                     int k, const float* x, const float* h_in, const float* bias,
+                     const float* c_in, float* c_out, float* h_out, hipStream_t st) {
+    if (H % 4 || I % 4 || 4 * H > INT32_MAX) return BS_ERR_UNSUPPORTED;
+    const LstmPart part{h_in, bias, c_in, c_out, h_out, (int)H, (int)I};
+    return launch_common(vals, idx, dtype, 4 * H, I + H, bank, k, x, nullptr, 0, 0, &part, nullptr,
+                         nullptr, st);
 }
 
 }  // namespace bs

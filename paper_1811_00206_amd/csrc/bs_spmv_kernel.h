@@ -47,9 +47,20 @@ struct SpmvArgs {
                             // 2: anything else
     int table_off;          // > 0: float index in LDS of the per-entry bank table
                             // (row_len words behind x); 0: no table, arithmetic path
+
+    // LSTM step only (spmv_kernel<..., true>): the matrix is the stacked gate matrix
+    // 4H x (I + H), the input vector is [x ; h_in], y is not written
+    const float* h_in;      // H floats
+    const float* bias;      // 4H floats, gate blocks i, f, g, o
+    const float* c_in;      // H floats
+    float* c_out;           // H floats (may be c_in)
+    float* h_out;           // H floats (not h_in: other workgroups still read it)
+    int H, I;
+    int pre_off;            // float index in LDS of the workgroup's rows_per_wg pre-activations
 };
 
 struct SpmvLaunch {
+    bool lstm;                      // fused LSTM cell update instead of storing y
     int threads;
     int grid;
     size_t lds;
@@ -171,9 +182,14 @@ __device__ __forceinline__ float consume_any(const SpmvArgs& a, const float* xs,
     return consume<VT, CH, LPR, U, 2>(a, xs, v, o, c0, round_base, cpr);
 }
 
+__device__ __forceinline__ float logistic(float v) { return 1.f / (1.f + expf(-v)); }
+
 // VT: storage type of vals; CH: entries per chunk (CH*sizeof(VT) <= 16, CH divides
 // row_len); LPR: lanes per row; U: chunks a lane keeps in flight per round.
-template <typename VT, int CH, int LPR, int U>
+// LSTM: the rows are the four gate pre-activations of hidden units and the kernel
+// ends with the cell update (the model of Sec. 4.3; bias as in eq. (1)) instead of
+// storing y: a workgroup owns rows_per_wg/4 units, its row i is gate i%4 of unit i/4.
+template <typename VT, int CH, int LPR, int U, bool LSTM = false>
 __global__ __launch_bounds__(1024) void spmv_kernel(SpmvArgs a) {
     extern __shared__ __align__(16) float xs[];
     using VRaw = typename RawBytes<CH * sizeof(VT)>::type;
@@ -182,8 +198,16 @@ __global__ __launch_bounds__(1024) void spmv_kernel(SpmvArgs a) {
     const int nthr = blockDim.x;
     const int lane_in_row = tid % LPR;
     const int row_in_wg = tid / LPR;
-    const int row = blockIdx.x * a.rows_per_wg + row_in_wg;
-    const bool live = row < a.M;
+    int row;
+    bool live;
+    if constexpr (LSTM) {
+        const int unit = blockIdx.x * (a.rows_per_wg >> 2) + (row_in_wg >> 2);
+        live = unit < a.H;
+        row = (row_in_wg & 3) * a.H + unit;
+    } else {
+        row = blockIdx.x * a.rows_per_wg + row_in_wg;
+        live = row < a.M;
+    }
     const int rowc = live ? row : a.M - 1;   // clamp: dead lanes load valid memory
 
     const VRaw* vrow = reinterpret_cast<const VRaw*>(
@@ -202,10 +226,16 @@ __global__ __launch_bounds__(1024) void spmv_kernel(SpmvArgs a) {
         const int wave = tid >> 6, lane = tid & 63, n_waves = nthr >> 6;
         for (int p = wave; p * 64 < K4; p += n_waves) {
             const int i = p * 64 + lane;
-            if (i < K4)
+            if (i < K4) {
+                const float4* src = x4 + i;
+                if constexpr (LSTM) {   // [x ; h_in]: I and H are multiples of 4 here
+                    const int I4 = a.I >> 2;
+                    if (i >= I4) src = reinterpret_cast<const float4*>(a.h_in) + (i - I4);
+                }
                 __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(x4 + i),
+                    (const __attribute__((address_space(1))) void*)src,
                     (__attribute__((address_space(3))) void*)(xs + p * 256), 16, 0, 0);
+            }
         }
     }
 
@@ -252,12 +282,29 @@ __global__ __launch_bounds__(1024) void spmv_kernel(SpmvArgs a) {
     }
 
     acc = group_sum<LPR>(acc);
-    if (live && lane_in_row == 0) a.y[row] = acc;
+    if constexpr (LSTM) {
+        // the four pre-activations of a unit meet in LDS; one lane per unit finishes it
+        float* pre = xs + a.pre_off;
+        if (lane_in_row == 0) pre[row_in_wg] = acc;
+        __syncthreads();
+        const int unit = blockIdx.x * (a.rows_per_wg >> 2) + tid;
+        if (tid < (a.rows_per_wg >> 2) && unit < a.H) {
+            const float gi = logistic(pre[4 * tid + 0] + a.bias[unit]);
+            const float gf = logistic(pre[4 * tid + 1] + a.bias[a.H + unit]);
+            const float gg = tanhf(pre[4 * tid + 2] + a.bias[2 * a.H + unit]);
+            const float go = logistic(pre[4 * tid + 3] + a.bias[3 * a.H + unit]);
+            const float c = fmaf(gf, a.c_in[unit], gi * gg);
+            a.c_out[unit] = c;
+            a.h_out[unit] = go * tanhf(c);
+        }
+    } else {
+        if (live && lane_in_row == 0) a.y[row] = acc;
+    }
 }
 
-template <typename VT, int CH, int LPR, int U>
+template <typename VT, int CH, int LPR, int U, bool LSTM = false>
 int spmv_launch_one(const SpmvArgs& a, const SpmvLaunch& l) {
-    auto kern = spmv_kernel<VT, CH, LPR, U>;
+    auto kern = spmv_kernel<VT, CH, LPR, U, LSTM>;
     if (l.lds > 48 * 1024) {
         static bool raised = false;   // per instantiation; raising it twice is harmless
         if (!raised) {
@@ -278,6 +325,13 @@ int spmv_launch_one(const SpmvArgs& a, const SpmvLaunch& l) {
 
 template <typename VT, int CH, int LPR>
 int spmv_launch_u(int u, const SpmvArgs& a, const SpmvLaunch& l) {
+    if (l.lstm) {   // the fused step is built for 8..64 lanes per row, 4 or 8 chunk slots
+        if constexpr (LPR >= 8) {
+            if (u == 4) return spmv_launch_one<VT, CH, LPR, 4, true>(a, l);
+            if (u == 8) return spmv_launch_one<VT, CH, LPR, 8, true>(a, l);
+        }
+        return BS_ERR_UNSUPPORTED;
+    }
     switch (u) {
         case 2: return spmv_launch_one<VT, CH, LPR, 2>(a, l);
         case 4: return spmv_launch_one<VT, CH, LPR, 4>(a, l);

@@ -85,6 +85,8 @@ WORKLOADS = {w.name: w for w in [
     _mk(6, "bench16k_k32", 16384, 8192, 256, 32, 1.0),
     _mk(6, "bench16k_k16", 16384, 8192, 256, 16, 1.0),
     _mk(6, "bench16k_k8", 16384, 8192, 256, 8, 1.0),
+    # Sec. 4.3's second recurrent model: hidden size 1024 (input size taken as 1024), 87.5 %
+    _mk(7, "bilstm1024", 4096, 2048, 64, 8, 0.05),
     _mk(6, "bench16k_k128_n8", 16384, 8192, 256, 128, 1.0, N=8),
     _mk(6, "bench16k_k32_n8", 16384, 8192, 256, 32, 1.0, N=8),
     _mk(6, "bench16k_k8_n8", 16384, 8192, 256, 8, 1.0, N=8),
@@ -110,6 +112,14 @@ def draw_activations(K: int, N: int, seed: int) -> np.ndarray:
     X = rng.random((K, N), dtype=np.float32)
     X = X * np.float32(2.0) - np.float32(1.0)
     return X[:, 0].copy() if N == 1 else X
+
+
+def draw_lstm_inputs(H: int, I: int, T: int, seed: int):
+    """Inputs of T LSTM steps besides the gate matrix: X [T, I] ~ U(-1, 1), h0 [H] and
+    c0 [H] ~ U(-1, 1), bias [4H] ~ U(-0.5, 0.5), all fp32."""
+    rng = np.random.Generator(np.random.PCG64(seed + 104729))
+    u = lambda shape, a: (rng.random(shape, dtype=np.float32) * np.float32(2 * a) - np.float32(a))
+    return u((T, I), 1.0), u((H,), 1.0), u((H,), 1.0), u((4 * H,), 0.5)
 
 
 def make(name_or_workload, rows: int | None = None):

@@ -235,6 +235,63 @@ def test_spmm_workspace_contract():
 
 # ------------------------------------------------------- dense baselines
 
+# ------------------------------------------------------------------- LSTM step
+
+def check_lstm(W, bank, k, H, I, T, seed, tol):
+    v, i = bs_ref.prune_pack(W, bank, k)
+    X, h0, c0, bias = workloads.draw_lstm_inputs(H, I, T, seed)
+    H_ref, c_ref = bs_ref.lstm_sequence(v, i, bank, X, h0, bias, c0)
+    vals, idx = dev(v), dev(i)
+    # one step through bs_lstm_step ...
+    c1, h1 = bs.bs_lstm_step(vals, idx, bank, dev(X[0]), dev(h0), dev(bias), dev(c0))
+    c1_ref, h1_ref = bs_ref.lstm_step(v, i, bank, X[0], h0, bias, c0)
+    assert bs_ref.rel_l2(host(c1), c1_ref) <= tol
+    assert bs_ref.rel_l2(host(h1), h1_ref) <= tol
+    assert np.abs(host(h1) - h1_ref).max() <= tol * 4      # |h| <= 1
+    # ... and the whole sequence, cell state updated in place
+    c = dev(c0)
+    H_all = bs.bs_lstm_sequence(vals, idx, bank, dev(X), dev(h0), dev(bias), c)
+    e_h, e_c = bs_ref.rel_l2(host(H_all).ravel(), H_ref.ravel()), bs_ref.rel_l2(host(c), c_ref)
+    say("  lstm", W.shape, bank, k, "T", T, "relL2 h", e_h, "c", e_c)
+    assert e_h <= tol and e_c <= tol
+    assert host(H_all)[0].tobytes() == host(h1).tobytes()      # same kernel, same order
+    return e_h
+
+
+@pytest.mark.parametrize("H,I,bank,k", [(8, 24, 16, 3), (12, 20, 8, 8), (4, 12, 4, 1),
+                                        (36, 64, 100, 10), (100, 60, 32, 5), (64, 448, 256, 77)])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_lstm_small(H, I, bank, k, dtype):
+    say("lstm small", H, I, bank, k, dtype)
+    W = workloads.draw_weights(4 * H, I + H, 0.3, dtype, 41)
+    check_lstm(W, bank, k, H, I, 5, 41, TOL[dtype])
+
+
+@pytest.mark.parametrize("name,H,I", [("lstm1500", 1500, 1500), ("bilstm1024", 1024, 1024)])
+def test_lstm_full_size(name, H, I):
+    """The recurrent models of Sec. 4.3 at full size, four steps."""
+    say("lstm full", name)
+    wl, W, _ = workloads.make(name)
+    assert wl.M == 4 * H and wl.K == I + H
+    check_lstm(W, wl.bank, wl.k, H, I, 4, wl.seed, TOL[wl.dtype])
+
+
+def test_lstm_refused_arguments():
+    H, I, bank, k = 8, 24, 16, 3
+    W = workloads.draw_weights(4 * H, I + H, 0.3, "f32", 42)
+    v, i = bs_ref.prune_pack(W, bank, k)
+    X, h0, c0, bias = workloads.draw_lstm_inputs(H, I, 1, 42)
+    vals, idx, x, h, b, c = dev(v), dev(i), dev(X[0]), dev(h0), dev(bias), dev(c0)
+    with pytest.raises(bs.BsError):      # hidden state updated in place: refused
+        bs.bs_lstm_step(vals, idx, bank, x, h, b, c, h_out=h)
+    # sizes that are not multiples of 4 are refused, not mis-computed
+    W2 = workloads.draw_weights(4 * 6, 10 + 6, 0.3, "f32", 43)
+    v2, i2 = bs_ref.prune_pack(W2, 8, 2)
+    X2, h2, c2, b2 = workloads.draw_lstm_inputs(6, 10, 1, 43)
+    with pytest.raises(bs.BsError):
+        bs.bs_lstm_step(dev(v2), dev(i2), 8, dev(X2[0]), dev(h2), dev(b2), dev(c2))
+
+
 def close_to_scale(Y, Y_ref, W, X, tol):
     """|error| <= tol * max_r sum_c |w_rc| |x_c|: an fp32 sum can lose that much
     when terms cancel, so tiny outputs are judged against the size of the terms."""

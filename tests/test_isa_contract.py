@@ -71,8 +71,9 @@ def kernels():
 
 def test_every_instantiation_is_present(kernels):
     # 3 chunk widths for fp32 + 4 for fp16, 7 group widths; 4 in-flight depths for
-    # SpMV; 5 group widths and 2 depths for SpMM
-    assert sum("spmv_kernel" in n for n in kernels) == (3 + 4) * 7 * 4
+    # SpMV, plus 4 group widths and 2 depths of the fused LSTM step; 5 group widths
+    # and 2 depths for SpMM
+    assert sum("spmv_kernel" in n for n in kernels) == (3 + 4) * 7 * 4 + (3 + 4) * 4 * 2
     assert sum("spmm_kernel" in n for n in kernels) == (3 + 4) * 5 * 2
 
 
