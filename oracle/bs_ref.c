@@ -155,6 +155,42 @@ int bs_ref_prune_pack_f16(const uint16_t *W, int64_t M, int64_t K, int B, int k,
     return BS_REF_OK;
 }
 
+/* ---------- re-prune a packed matrix to fewer weights per bank -----------
+ *
+ * One round of Algorithm 1's loop (Sec. 3.2: the sparsity is raised step by
+ * step) applied to the packed form, without the retraining between rounds:
+ * of the k stored weights of a bank the k2 <= k largest magnitudes stay, ties
+ * keep the lower offset (= the lower slot, offsets ascend), order unchanged.
+ * n_banks = M * (K/bank).  is_f16 selects the storage type of the values.
+ */
+int bs_ref_reprune(const void *vals, int is_f16, const uint8_t *idx, int64_t n_banks,
+                   int k, int k2, void *vals2, uint8_t *idx2)
+{
+    if (!vals || !idx || !vals2 || !idx2) return BS_REF_ERR_NULL;
+    if (n_banks < 1 || k < 1 || k > 256 || k2 < 1 || k2 > k) return BS_REF_ERR_SHAPE;
+    double mag[256];
+    unsigned char keep[256];
+    for (int64_t b = 0; b < n_banks; ++b) {
+        for (int t = 0; t < k; ++t) {
+            double v = is_f16 ? half_bits_to_double(((const uint16_t *)vals)[b * k + t])
+                              : (double)((const float *)vals)[b * k + t];
+            if (!isfinite(v)) return BS_REF_ERR_NONFINITE;
+            mag[t] = fabs(v);
+        }
+        bank_select(mag, k, k2, keep);
+        int u = 0;
+        for (int t = 0; t < k; ++t) {
+            if (!keep[t]) continue;
+            if (is_f16) ((uint16_t *)vals2)[b * k2 + u] = ((const uint16_t *)vals)[b * k + t];
+            else memcpy((float *)vals2 + b * k2 + u, (const float *)vals + b * k + t, sizeof(float));
+            idx2[b * k2 + u] = idx[b * k + t];
+            ++u;
+        }
+        if (u != k2) return BS_REF_ERR_SHAPE; /* cannot happen */
+    }
+    return BS_REF_OK;
+}
+
 /* ---------- unpack: the pruned dense matrix M_p of Algorithm 1 ----------- */
 
 int bs_ref_unpack_f32(const float *vals, const uint8_t *idx, int64_t M, int64_t K,

@@ -55,6 +55,7 @@ def _load():
         lib.bs_ref_spmm.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, i64, i64, vp, i64, i32]
         lib.bs_ref_spmv.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, vp, i32]
         lib.bs_ref_dense_gemm_f64.argtypes = [vp, i32, i64, i64, vp, i64, i64, vp, i64]
+        lib.bs_ref_reprune.argtypes = [vp, i32, vp, i64, i32, i32, vp, vp]
         lib.bs_ref_lstm_step.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp]
         lib.bs_ref_rel_l2.argtypes = [vp, vp, i64]
         lib.bs_ref_rel_l2.restype = ctypes.c_double
@@ -166,6 +167,19 @@ def spmv(vals, idx, bank: int, x, threads: int = 1) -> np.ndarray:
     if st:
         raise OracleError(st, "spmv")
     return y
+
+
+def reprune(vals, idx, k2: int):
+    """Keep the k2 largest magnitudes of the k stored per bank: (vals2, idx2) [M, nb, k2]."""
+    is16, vals = _storage(vals, "vals")
+    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    M, nb, k = vals.shape
+    vals2 = np.empty((M, nb, k2), dtype=vals.dtype)
+    idx2 = np.empty((M, nb, k2), dtype=np.uint8)
+    st = _load().bs_ref_reprune(_p(vals), is16, _p(idx), M * nb, k, int(k2), _p(vals2), _p(idx2))
+    if st:
+        raise OracleError(st, "reprune")
+    return vals2, idx2
 
 
 def lstm_step(vals, idx, bank: int, x, h, bias, c):

@@ -412,3 +412,32 @@ def test_lstm_sequence_is_the_step_repeated():
     c3, h3 = bs_ref.lstm_step(vals, idx, bank, X[2], h2, bias, c2)
     assert Hs[0].tobytes() == h1.tobytes() and Hs[1].tobytes() == h2.tobytes()
     assert Hs[2].tobytes() == h3.tobytes() and cT.tobytes() == c3.tobytes()
+
+
+# ------------------------------------------------------ re-prune of a packed matrix
+
+@pytest.mark.parametrize("M,K,bank,k", SHAPES)
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_reprune_equals_pruning_the_dense_matrix_directly(M, K, bank, k, dtype):
+    """Sec. 3.2 raises the sparsity step by step; without retraining the steps
+    commute with a one-shot prune (dropping the smallest never reorders the rest), so
+    re-pruning the packed form must give exactly what pruning W to k2 gives."""
+    W = rand_w(M, K, 51, dtype=dtype)
+    vals, idx = bs_ref.prune_pack(W, bank, k)
+    for k2 in sorted({1, max(1, k // 2), k}):
+        v2, i2 = bs_ref.reprune(vals, idx, k2)
+        v_ref, i_ref = bs_ref.prune_pack(W, bank, k2)
+        assert v2.tobytes() == v_ref.tobytes() and i2.tobytes() == i_ref.tobytes()
+
+
+def test_reprune_ties_and_library_definition():
+    W = workloads.tie_heavy_weights(6, 128, 3, "f32", 52)
+    vals, idx = bs_ref.prune_pack(W, 32, 12)
+    v2, i2 = bs_ref.reprune(vals, idx, 5)
+    # stable library sort over the 12 stored slots of each bank, a different algorithm
+    order = np.argsort(-np.abs(vals.astype(np.float64)), axis=2, kind="stable")[:, :, :5]
+    slots = np.sort(order, axis=2)
+    assert np.take_along_axis(vals, slots, axis=2).tobytes() == v2.tobytes()
+    assert np.take_along_axis(idx, slots, axis=2).tobytes() == i2.tobytes()
+    with pytest.raises(bs_ref.OracleError):
+        bs_ref.reprune(vals, idx, 13)        # cannot grow
