@@ -103,6 +103,10 @@ def region_us(torch, fn, n):
 
 OTHER_WORKLOADS = ("tiny", "sweep_k32", "sweep_k16", "sweep_k8", "sweep_k4", "sweep_k2",
                    "lstm1500_n8", "lstm1500_n32", "lstm1500_n128", "fc6_b1", "fc6_b16",
+                   # Table 4's axes: balance range 25 / 50 / 100 at 60 % .. 80 % on the LSTM matrix
+                   "lstm1500_b25_k10", "lstm1500_b25_k5", "lstm1500_b50_k20", "lstm1500_b50_k15",
+                   "lstm1500_b50_k10", "lstm1500_b100_k40", "lstm1500_b100_k30", "lstm1500_b100_k20",
+                   "bilstm1024",
                    # Sec. 4.1's matrix shape, 50 % .. 97 % sparse, batch 1 and 8
                    "bench16k_k128", "bench16k_k64", "bench16k_k32", "bench16k_k16", "bench16k_k8",
                    "bench16k_k128_n8", "bench16k_k32_n8", "bench16k_k8_n8")
@@ -370,6 +374,13 @@ def main():
         p_bytes = W.nbytes + wl.nnz * (wl.val_bytes + 1)
         extras["prune_pack_us"] = round(p_us, 1)
         extras["prune_pack_GBps"] = round(p_bytes / p_us / 1e3, 1)
+        # one more pruning round on the packed matrix: half the weights of every bank
+        if wl.k >= 2:
+            k2 = wl.k // 2
+            r_us = avg_us(lambda i: bs.bs_reprune(vals, idx, wl.bank, k2), 10)
+            extras["reprune_to_half_us"] = round(r_us, 1)
+            extras["reprune_GBps"] = round((wl.nnz + wl.M * (wl.K // wl.bank) * k2) *
+                                           (wl.val_bytes + 1) / r_us / 1e3, 1)
         ev.close()
 
         # fused LSTM time steps (Sec. 4.3's language model: H = I = 1500 is this very gate

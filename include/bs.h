@@ -76,6 +76,20 @@ const char* bs_status_str(int status);
 int bs_prune_pack(const void* W, int dtype, int64_t M, int64_t K, int bank, int k,
                   void* vals, uint8_t* idx, void* stream);
 
+/*
+ * Re-prune a packed matrix to k2 <= k weights per bank: one more round of
+ * Algorithm 1's loop (Sec. 3.2 raises the sparsity step by step), without the
+ * retraining between rounds.  Of the k stored weights of every bank the k2
+ * largest magnitudes stay (ties keep the lower offset), in ascending offset.
+ * The result is bit-identical to bs_prune_pack(W, ..., k2) on the matrix the
+ * packed one came from.
+ * vals, idx    DEVICE in   packed matrix [M][K/bank][k]
+ * vals2, idx2  DEVICE out  packed matrix [M][K/bank][k2]; must not overlap the inputs
+ * k2 > k returns BS_ERR_SHAPE.
+ */
+int bs_reprune(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K,
+               int bank, int k, int k2, void* vals2, uint8_t* idx2, void* stream);
+
 /* ---- y = W_sparse . x  (Sec. 3.4, batch size 1; eq. (1) with zero bias) --- */
 
 /*

@@ -21,7 +21,7 @@ BS_F32, BS_F16 = 0, 1
 EXPORTS = (
     "bs_nnz", "bs_vals_bytes", "bs_idx_bytes", "bs_status_str", "bs_prune_pack", "bs_spmv",
     "bs_spmv_ex", "bs_spmm_workspace_bytes", "bs_spmm", "bs_dense_gemv", "bs_dense_gemm",
-    "bs_lstm_step", "bs_lstm_sequence",
+    "bs_lstm_step", "bs_lstm_sequence", "bs_reprune",
 )
 
 
@@ -65,10 +65,11 @@ def load_library():
     lib.bs_spmm.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, i64, vp, i64, vp, sz, vp]
     lib.bs_dense_gemv.argtypes = [vp, i32, i64, i64, vp, vp, vp]
     lib.bs_dense_gemm.argtypes = [vp, i32, i64, i64, vp, i64, i64, vp, i64, vp]
+    lib.bs_reprune.argtypes = [vp, vp, i32, i64, i64, i32, i32, i32, vp, vp, vp]
     lib.bs_lstm_step.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.bs_lstm_sequence.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, vp, vp, vp, vp, vp]
     for name in ("bs_prune_pack", "bs_spmv", "bs_spmv_ex", "bs_spmm", "bs_dense_gemv",
-                 "bs_dense_gemm", "bs_lstm_step", "bs_lstm_sequence"):
+                 "bs_dense_gemm", "bs_lstm_step", "bs_lstm_sequence", "bs_reprune"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -309,3 +310,16 @@ def bs_lstm_sequence(vals, idx, bank: int, X, h0, bias, c, H_all=None):
                                            _ptr(h0), _ptr(bias), _ptr(c), _ptr(H_all), _stream()),
            "bs_lstm_sequence")
     return H_all
+
+
+def bs_reprune(vals, idx, bank: int, k2: int):
+    """Packed [M, K/bank, k] -> packed [M, K/bank, k2], k2 <= k: (vals2, idx2)."""
+    code, M, K, k = _packed(vals, idx, bank)
+    if k2 < 1 or k2 > k:
+        raise BsError(2, "bs_reprune")
+    nb = K // bank
+    vals2 = torch.empty((M, nb, k2), dtype=vals.dtype, device=vals.device)
+    idx2 = torch.empty((M, nb, k2), dtype=torch.uint8, device=vals.device)
+    _check(load_library().bs_reprune(_ptr(vals), _ptr(idx), code, M, K, bank, k, k2, _ptr(vals2),
+                                     _ptr(idx2), _stream()), "bs_reprune")
+    return vals2, idx2

@@ -65,6 +65,18 @@ int bs_prune_pack(const void* W, int dtype, int64_t M, int64_t K, int bank, int 
                                  static_cast<hipStream_t>(stream));
 }
 
+int bs_reprune(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
+               int k, int k2, void* vals2, uint8_t* idx2, void* stream) {
+    int st = check_packed(vals, idx, dtype, M, K, bank, k);
+    if (st) return st;
+    if (k2 < 1 || k2 > k) return BS_ERR_SHAPE;
+    st = check_packed(vals2, static_cast<const uint8_t*>(idx2), dtype, M, K, bank, k2);
+    if (st) return st;
+    if (vals2 == vals || idx2 == idx) return BS_ERR_UNSUPPORTED;
+    return bs::launch_reprune(vals, idx, dtype, M * (K / bank), k, k2, vals2, idx2,
+                              static_cast<hipStream_t>(stream));
+}
+
 int bs_spmv_ex(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
                int k, const float* x, float* y, int lanes_per_row, int rows_per_wg,
                void* start_event, void* stop_event, void* stream) {

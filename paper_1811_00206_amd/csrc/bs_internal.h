@@ -18,6 +18,8 @@ constexpr int kMaxLdsBytes = 160 * 1024;   // LDS of one gfx950 compute unit
 // Launchers (host).  Arguments are already validated by the C-ABI layer.
 int launch_prune_pack(const void* W, int dtype, int64_t M, int64_t K, int bank, int k,
                       void* vals, uint8_t* idx, hipStream_t st);
+int launch_reprune(const void* vals, const uint8_t* idx, int dtype, int64_t n_banks, int k, int k2,
+                   void* vals2, uint8_t* idx2, hipStream_t st);
 int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
                 int k, const float* x, float* y, int lanes_per_row, int rows_per_wg,
                 hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st);

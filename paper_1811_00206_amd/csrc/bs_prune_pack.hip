@@ -3,28 +3,24 @@
 // "order by absolute magnitude, drop the smallest" step, taken in one shot to
 // exactly k survivors per bank).
 //
-// One wavefront owns one bank at a time; lane l holds the bank's elements at
-// offsets l, l+64, ... (S = ceil(B/64) of them).  Selection never sorts and
-// never touches floating point:
+// Selection never sorts and never touches floating point:
 //   * key = bit pattern of |w| (monotone in |w| for finite values);
-//   * the k-th largest key T is built bit by bit from the top: T |= bit if at
-//     least k keys are >= T|bit (one ballot + popcount per 64 elements);
+//   * the k-th largest key T is built bit by bit from the top: the bit is set if
+//     at least k keys have the prefix built so far with that bit set;
 //   * every key > T survives; of the keys == T the first k - #(key > T) in
-//     offset order survive (ballot + count of set lanes below), which is the
-//     lower-offset tie rule;
-//   * survivors get their output slot from the same prefix count, so offsets
-//     come out ascending; values are copied bit for bit.
+//     offset order survive, which is the lower-offset tie rule;
+//   * survivors get their output slot from prefix counts in offset order, so
+//     offsets come out ascending; values are copied bit for bit.
 // Algorithm 1 compares against a threshold with "<", which would keep every
-// element tied with the threshold; the prefix count keeps exactly k instead.
+// element tied with the threshold; counting keeps exactly k instead.
 //
-// Two kernels share that selection rule:
-//   * prune_pack_lanes (bank sizes whose byte length is a multiple of 16): LPB
-//     lanes share a bank and hold it in registers as R 16-byte pieces each, so a
-//     wavefront works on 64/LPB banks at once.  The keys are bit-sliced in
-//     registers, so a pass over one bit costs one AND and one popcount for all
-//     32 elements of a lane, plus a DPP sum over the LPB lanes.
-//   * prune_pack_kernel (any bank size): one bank per wavefront, counts by
-//     ballot + scalar popcount.
+// prune_pack_lanes: LPB lanes share a bank and hold it in registers as R pieces of
+// 16 bytes each (8, 4 or 2 bytes when the bank's byte length is not a multiple of
+// 16), so a wavefront works on 64/LPB banks at once.  The keys are bit-sliced in
+// registers, so a pass over one bit costs one AND and one popcount for all 32
+// elements of a lane, plus a DPP sum over the LPB lanes.
+// Re-pruning a packed matrix to fewer weights per bank (one more round of
+// Algorithm 1's loop) runs the same kernels on the stored values, k per bank.
 #include "bs_internal.h"
 
 namespace bs {
@@ -33,72 +29,6 @@ namespace {
 template <typename VT> struct Bits;
 template <> struct Bits<float> { using type = uint32_t; static constexpr int mag_bits = 31; };
 template <> struct Bits<__half> { using type = uint16_t; static constexpr int mag_bits = 15; };
-
-// S = elements per lane (bank <= 64*S)
-template <typename VT, int S>
-__global__ __launch_bounds__(256) void prune_pack_kernel(const VT* __restrict__ W,
-                                                         VT* __restrict__ vals,
-                                                         uint8_t* __restrict__ idx,
-                                                         int64_t n_banks, int B, int k) {
-    using U = typename Bits<VT>::type;
-    constexpr int NB = Bits<VT>::mag_bits;
-    const U* Wb = reinterpret_cast<const U*>(W);
-    U* vb = reinterpret_cast<U*>(vals);
-
-    const int lane = threadIdx.x & (kWave - 1);
-    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
-    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) / kWave;
-
-    for (int64_t g = wave; g < n_banks; g += n_waves) {
-        const U* src = Wb + g * B;
-        U raw[S];
-        uint32_t key[S];
-        bool valid[S];
-#pragma unroll
-        for (int s = 0; s < S; ++s) {
-            int o = s * kWave + lane;
-            valid[s] = o < B;
-            raw[s] = valid[s] ? src[o] : (U)0;
-            key[s] = (uint32_t)raw[s] & ((1u << NB) - 1u);
-        }
-
-        // k-th largest key, most significant bit first
-        uint32_t T = 0;
-#pragma unroll 1
-        for (int bit = NB - 1; bit >= 0; --bit) {
-            uint32_t cand = T | (1u << bit);
-            int c = 0;
-#pragma unroll
-            for (int s = 0; s < S; ++s)
-                c += __popcll(__ballot(valid[s] && key[s] >= cand));
-            if (c >= k) T = cand;
-        }
-
-        int n_gt = 0;
-#pragma unroll
-        for (int s = 0; s < S; ++s) n_gt += __popcll(__ballot(valid[s] && key[s] > T));
-        const int need = k - n_gt;   // how many of the keys equal to T survive (>= 1)
-
-        int eq_before = 0, kept_before = 0;
-        const int64_t out = g * k;
-#pragma unroll
-        for (int s = 0; s < S; ++s) {
-            bool eq = valid[s] && key[s] == T;
-            bool gt = valid[s] && key[s] > T;
-            uint64_t m_eq = __ballot(eq);
-            bool keep = gt || (eq && eq_before + lanes_below(m_eq) < need);
-            uint64_t m_keep = __ballot(keep);
-            if (keep) {
-                int slot = kept_before + lanes_below(m_keep);
-                vb[out + slot] = raw[s];
-                idx[out + slot] = (uint8_t)(s * kWave + lane);
-            }
-            eq_before += __popcll(m_eq);
-            kept_before += __popcll(m_keep);
-        }
-    }
-}
-
 
 // ---- bit-sliced selection ---------------------------------------------------
 // 32 x 32 bit-matrix transpose in registers (five block-swap stages): afterwards
@@ -136,8 +66,10 @@ __device__ __forceinline__ uint32_t low_bits(int n, int word) {
     return m <= 0 ? 0u : m >= 32 ? 0xFFFFFFFFu : ((1u << m) - 1u);
 }
 
-// LPB lanes per bank, R pieces of 16 bytes per lane; piece p = q + LPB*j holds the
-// offsets [p*E, p*E + E), E = 16 / sizeof(VT).  Requires B % E == 0.
+// LPB lanes per bank, R pieces of PB bytes per lane (PB = 16, or 8 / 4 / 2 when the
+// byte size of a bank is not a multiple of 16, so that every bank still starts on a
+// piece boundary); piece p = q + LPB*j holds the offsets [p*E, p*E + E),
+// E = PB / sizeof(VT).  Requires B % E == 0.
 //
 // A lane numbers its own elements e = j*E + i (ascending offset) and keeps sets of
 // them as bit masks (one word for up to 32 elements, two for binary16's 64).  The
@@ -150,19 +82,21 @@ __device__ __forceinline__ uint32_t low_bits(int n, int word) {
 // At the end `cand` are the keys equal to the threshold.  If a bank has more of them
 // than open slots, the cut between kept and dropped ties is an offset C, found the
 // same way (8 bits): the lane's elements below an offset are its lowest bits.
-template <typename VT, int LPB, int R>
+template <typename VT, int PB, int LPB, int R>
 __global__ __launch_bounds__(256) void prune_pack_lanes(const VT* __restrict__ W,
                                                         VT* __restrict__ vals,
                                                         uint8_t* __restrict__ idx,
+                                                        const uint8_t* __restrict__ remap,
                                                         int64_t n_banks, int B, int k) {
     using U = typename Bits<VT>::type;
     constexpr int NB = Bits<VT>::mag_bits;
-    constexpr int E = 16 / sizeof(VT);
+    using Raw = typename RawBytes<PB>::type;
+    constexpr int E = PB / sizeof(VT);            // elements per piece
     constexpr int NE = R * E;                     // elements per lane
     constexpr int NM = NE > 32 ? 2 : 1;           // mask words
     constexpr int BPW = kWave / LPB;              // banks per wavefront
     constexpr int LOG_LPB = LPB == 1 ? 0 : LPB == 2 ? 1 : LPB == 4 ? 2 : LPB == 8 ? 3 : 4;
-    constexpr int LOG_E = E == 4 ? 2 : 3;
+    constexpr int LOG_E = E == 1 ? 0 : E == 2 ? 1 : E == 4 ? 2 : 3;
     static_assert(LPB <= 16 && NE <= 64, "lane shape");
 
     const int lane = threadIdx.x & (kWave - 1);
@@ -182,9 +116,9 @@ __global__ __launch_bounds__(256) void prune_pack_lanes(const VT* __restrict__ W
     for (int64_t grp = wave; grp < n_groups; grp += n_waves) {
         const int64_t g = grp * BPW + lane / LPB;     // this lane's bank
         const bool bank_ok = g < n_banks;
-        const uint4* src = reinterpret_cast<const uint4*>(W + (bank_ok ? g : n_banks - 1) * B);
+        const Raw* src = reinterpret_cast<const Raw*>(W + (bank_ok ? g : n_banks - 1) * B);
 
-        uint4 raw[R];
+        Raw raw[R];
         uint32_t valid[NM];
 #pragma unroll
         for (int m = 0; m < NM; ++m) valid[m] = 0u;
@@ -204,9 +138,11 @@ __global__ __launch_bounds__(256) void prune_pack_lanes(const VT* __restrict__ W
                 w[e] = e < NE ? word_of(raw[e / E], e % E) : 0u;
             } else {
                 uint32_t lo = 0u, hi = 0u;
-                if (e < NE) lo = (word_of(raw[e / E], (e % E) >> 1) >> (16 * (e & 1))) & 0xffffu;
+                if (e < NE)
+                    lo = (word_of(raw[e / E], (e % E) >> 1) >> (16 * ((e % E) & 1))) & 0xffffu;
                 if (e + 32 < NE)
-                    hi = (word_of(raw[(e + 32) / E], ((e + 32) % E) >> 1) >> (16 * (e & 1))) & 0xffffu;
+                    hi = (word_of(raw[(e + 32) / E], ((e + 32) % E) >> 1) >>
+                          (16 * (((e + 32) % E) & 1))) & 0xffffu;
                 w[e] = lo | (hi << 16);
             }
         }
@@ -297,7 +233,7 @@ __global__ __launch_bounds__(256) void prune_pack_lanes(const VT* __restrict__ W
                     uint32_t v = word_of(raw[j], sizeof(VT) == 4 ? i : i >> 1);
                     if (sizeof(VT) == 2) v = (i & 1) ? (v >> 16) : (v & 0xffffu);
                     lds_v[slot] = (U)v;
-                    lds_i[slot] = (uint8_t)(off0 + i);
+                    lds_i[slot] = remap ? remap[g * B + off0 + i] : (uint8_t)(off0 + i);
                     ++slot;
                 }
             }
@@ -328,79 +264,95 @@ __global__ __launch_bounds__(256) void prune_pack_lanes(const VT* __restrict__ W
     }
 }
 
-template <typename VT, int LPB>
-int launch_lanes_r(int r, const VT* w, VT* v, uint8_t* idx, int64_t n_banks, int bank, int k,
-                   hipStream_t st) {
-    const int threads = 256;
-    const int64_t groups = (n_banks + (kWave / LPB) - 1) / (kWave / LPB);
-    int64_t grid = (groups + threads / kWave - 1) / (threads / kWave);
-    const int64_t cap = 256 * 16;
-    if (grid > cap) grid = cap;
-    const size_t lds = (size_t)(threads / kWave) * (kWave / LPB) * k * (sizeof(VT) + 1);
-#define BS_PP_CASE(RR) case RR: hipLaunchKernelGGL((prune_pack_lanes<VT, LPB, RR>), dim3((unsigned)grid), dim3(threads), lds, st, w, v, idx, n_banks, bank, k); break;
-    switch (r) {
-        BS_PP_CASE(1) BS_PP_CASE(2) BS_PP_CASE(3) BS_PP_CASE(4)
-        BS_PP_CASE(5) BS_PP_CASE(6) BS_PP_CASE(7) BS_PP_CASE(8)
-        default: return BS_ERR_UNSUPPORTED;
+template <typename VT, int PB, int LPB, int R>
+int launch_shape(const VT* w, VT* v, uint8_t* idx, const uint8_t* remap, int64_t n_banks, int bank,
+                 int k, hipStream_t st) {
+    constexpr int E = PB / (int)sizeof(VT);
+    if constexpr (R * E > 64 || (sizeof(VT) == 4 && R * E > 32)) {
+        return BS_ERR_UNSUPPORTED;   // not a shape the planner below produces
+    } else {
+        const int threads = 256;
+        const int64_t groups = (n_banks + (kWave / LPB) - 1) / (kWave / LPB);
+        int64_t grid = (groups + threads / kWave - 1) / (threads / kWave);
+        const int64_t cap = 256 * 16;
+        if (grid > cap) grid = cap;
+        const size_t lds = (size_t)(threads / kWave) * (kWave / LPB) * k * (sizeof(VT) + 1);
+        hipLaunchKernelGGL((prune_pack_lanes<VT, PB, LPB, R>), dim3((unsigned)grid), dim3(threads),
+                           lds, st, w, v, idx, remap, n_banks, bank, k);
+        return hip_status(hipGetLastError());
     }
-#undef BS_PP_CASE
-    return hip_status(hipGetLastError());
 }
 
-template <typename VT>
-int launch_lanes(const void* W, int64_t n_banks, int bank, int k, void* vals, uint8_t* idx,
-                 hipStream_t st) {
-    constexpr int E = 16 / sizeof(VT);
+template <typename VT, int PB, int LPB>
+int launch_r(int r, const VT* w, VT* v, uint8_t* idx, const uint8_t* remap, int64_t n_banks,
+             int bank, int k, hipStream_t st) {
+#define BS_PP_CASE(RR) case RR: return launch_shape<VT, PB, LPB, RR>(w, v, idx, remap, n_banks, bank, k, st);
+    if constexpr (PB == 16) {
+        switch (r) {
+            BS_PP_CASE(1) BS_PP_CASE(2) BS_PP_CASE(3) BS_PP_CASE(4)
+            BS_PP_CASE(5) BS_PP_CASE(6) BS_PP_CASE(7) BS_PP_CASE(8)
+        }
+    } else {   // narrow pieces: fewer shapes, unused pieces are masked
+        switch (r) { BS_PP_CASE(4) BS_PP_CASE(8) BS_PP_CASE(16) BS_PP_CASE(32) }
+    }
+#undef BS_PP_CASE
+    return BS_ERR_UNSUPPORTED;
+}
+
+template <typename VT, int PB>
+int launch_pb(const void* W, int64_t n_banks, int bank, int k, void* vals, uint8_t* idx,
+              const uint8_t* remap, hipStream_t st) {
+    constexpr int E = PB / (int)sizeof(VT);
+    constexpr int kMaxPerLane = (sizeof(VT) == 4 ? 32 : 64) / E;   // elements fit the lane's masks
+    constexpr int r_max = PB == 16 ? 8 : (kMaxPerLane < 32 ? kMaxPerLane : 32);
     const int pieces = bank / E;
     int lpb = 1;
-    while (lpb < kWave && (pieces + lpb - 1) / lpb > 8) lpb <<= 1;
-    const int r = (pieces + lpb - 1) / lpb;
+    while (lpb < 16 && (pieces + lpb - 1) / lpb > r_max) lpb <<= 1;
+    int r = (pieces + lpb - 1) / lpb;
+    if (r > r_max) return BS_ERR_UNSUPPORTED;
+    if (PB != 16) r = r <= 4 ? 4 : r <= 8 ? 8 : r <= 16 ? 16 : 32;
     const VT* w = static_cast<const VT*>(W);
     VT* v = static_cast<VT*>(vals);
     switch (lpb) {
-        case 1: return launch_lanes_r<VT, 1>(r, w, v, idx, n_banks, bank, k, st);
-        case 2: return launch_lanes_r<VT, 2>(r, w, v, idx, n_banks, bank, k, st);
-        case 4: return launch_lanes_r<VT, 4>(r, w, v, idx, n_banks, bank, k, st);
-        case 8: return launch_lanes_r<VT, 8>(r, w, v, idx, n_banks, bank, k, st);
-        case 16: return launch_lanes_r<VT, 16>(r, w, v, idx, n_banks, bank, k, st);
+        case 1: return launch_r<VT, PB, 1>(r, w, v, idx, remap, n_banks, bank, k, st);
+        case 2: return launch_r<VT, PB, 2>(r, w, v, idx, remap, n_banks, bank, k, st);
+        case 4: return launch_r<VT, PB, 4>(r, w, v, idx, remap, n_banks, bank, k, st);
+        case 8: return launch_r<VT, PB, 8>(r, w, v, idx, remap, n_banks, bank, k, st);
+        case 16: return launch_r<VT, PB, 16>(r, w, v, idx, remap, n_banks, bank, k, st);
     }
     return BS_ERR_UNSUPPORTED;
 }
 
+// W viewed as n_banks banks of `bank` elements, k kept per bank
 template <typename VT>
-int launch_t(const void* W, int64_t n_banks, int bank, int k, void* vals, uint8_t* idx,
-             hipStream_t st) {
-    const int threads = 256;
-    const int waves_per_wg = threads / kWave;
-    // enough workgroups to fill 256 compute units several times over, at most one bank per wave
-    int64_t grid = (n_banks + waves_per_wg - 1) / waves_per_wg;
-    const int64_t cap = 256 * 32;
-    if (grid > cap) grid = cap;
-    const VT* w = static_cast<const VT*>(W);
-    VT* v = static_cast<VT*>(vals);
-    const int S = (bank + kWave - 1) / kWave;
-    switch (S) {
-        case 1: hipLaunchKernelGGL((prune_pack_kernel<VT, 1>), dim3((unsigned)grid), dim3(threads), 0, st, w, v, idx, n_banks, bank, k); break;
-        case 2: hipLaunchKernelGGL((prune_pack_kernel<VT, 2>), dim3((unsigned)grid), dim3(threads), 0, st, w, v, idx, n_banks, bank, k); break;
-        case 3: hipLaunchKernelGGL((prune_pack_kernel<VT, 3>), dim3((unsigned)grid), dim3(threads), 0, st, w, v, idx, n_banks, bank, k); break;
-        case 4: hipLaunchKernelGGL((prune_pack_kernel<VT, 4>), dim3((unsigned)grid), dim3(threads), 0, st, w, v, idx, n_banks, bank, k); break;
-        default: return BS_ERR_UNSUPPORTED;
-    }
-    return hip_status(hipGetLastError());
+int prune_banks_t(const void* W, int64_t n_banks, int bank, int k, void* vals, uint8_t* idx,
+                  const uint8_t* remap, hipStream_t st) {
+    const int bytes = bank * (int)sizeof(VT);   // widest piece that every bank starts on
+    if (bytes % 16 == 0) return launch_pb<VT, 16>(W, n_banks, bank, k, vals, idx, remap, st);
+    if (bytes % 8 == 0) return launch_pb<VT, 8>(W, n_banks, bank, k, vals, idx, remap, st);
+    if (bytes % 4 == 0) return launch_pb<VT, 4>(W, n_banks, bank, k, vals, idx, remap, st);
+    if constexpr (sizeof(VT) == 2) return launch_pb<VT, 2>(W, n_banks, bank, k, vals, idx, remap, st);
+    return BS_ERR_UNSUPPORTED;
+}
+
+int prune_banks(const void* W, int dtype, int64_t n_banks, int bank, int k, void* vals, uint8_t* idx,
+                const uint8_t* remap, hipStream_t st) {
+    if (dtype == BS_F16) return prune_banks_t<__half>(W, n_banks, bank, k, vals, idx, remap, st);
+    return prune_banks_t<float>(W, n_banks, bank, k, vals, idx, remap, st);
 }
 
 }  // namespace
 
 int launch_prune_pack(const void* W, int dtype, int64_t M, int64_t K, int bank, int k,
                       void* vals, uint8_t* idx, hipStream_t st) {
-    const int64_t n_banks = M * (K / bank);
-    const int vsize = dtype == BS_F16 ? 2 : 4;
-    if ((bank * vsize) % 16 == 0) {   // every bank starts on a 16-byte boundary
-        if (dtype == BS_F16) return launch_lanes<__half>(W, n_banks, bank, k, vals, idx, st);
-        return launch_lanes<float>(W, n_banks, bank, k, vals, idx, st);
-    }
-    if (dtype == BS_F16) return launch_t<__half>(W, n_banks, bank, k, vals, idx, st);
-    return launch_t<float>(W, n_banks, bank, k, vals, idx, st);
+    return prune_banks(W, dtype, M * (K / bank), bank, k, vals, idx, nullptr, st);
+}
+
+// Re-prune: the k stored values of a bank are a bank of k elements themselves; the
+// survivors carry the offsets the packed matrix already holds instead of their slots.
+int launch_reprune(const void* vals, const uint8_t* idx, int dtype, int64_t n_banks, int k, int k2,
+                   void* vals2, uint8_t* idx2, hipStream_t st) {
+    return prune_banks(vals, dtype, n_banks, k, k2, vals2, idx2, idx, st);
 }
 
 }  // namespace bs

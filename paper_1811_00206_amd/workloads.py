@@ -85,6 +85,15 @@ WORKLOADS = {w.name: w for w in [
     _mk(6, "bench16k_k32", 16384, 8192, 256, 32, 1.0),
     _mk(6, "bench16k_k16", 16384, 8192, 256, 16, 1.0),
     _mk(6, "bench16k_k8", 16384, 8192, 256, 8, 1.0),
+    # Table 4's axes on the LSTM gate matrix: balance range 25 / 50 / 100 at 60 % .. 80 %
+    _mk(8, "lstm1500_b25_k10", 6000, 3000, 25, 10, 0.05),
+    _mk(8, "lstm1500_b25_k5", 6000, 3000, 25, 5, 0.05),
+    _mk(8, "lstm1500_b50_k20", 6000, 3000, 50, 20, 0.05),
+    _mk(8, "lstm1500_b50_k15", 6000, 3000, 50, 15, 0.05),
+    _mk(8, "lstm1500_b50_k10", 6000, 3000, 50, 10, 0.05),
+    _mk(8, "lstm1500_b100_k40", 6000, 3000, 100, 40, 0.05),
+    _mk(8, "lstm1500_b100_k30", 6000, 3000, 100, 30, 0.05),
+    _mk(8, "lstm1500_b100_k20", 6000, 3000, 100, 20, 0.05),
     # Sec. 4.3's second recurrent model: hidden size 1024 (input size taken as 1024), 87.5 %
     _mk(7, "bilstm1024", 4096, 2048, 64, 8, 0.05),
     _mk(6, "bench16k_k128_n8", 16384, 8192, 256, 128, 1.0, N=8),

@@ -81,8 +81,52 @@ def test_prune_pack_special_values():
         check_pack(Wh, bank, k)
 
 
+@pytest.mark.parametrize("M,K,bank,k", SMALL_SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_reprune_small(M, K, bank, k, dtype):
+    """Every k2 from 1 to k: bit-exact against the oracle's re-prune (which is pinned to
+    the one-shot prune of the dense matrix)."""
+    say("reprune", M, K, bank, k, dtype)
+    W = workloads.draw_weights(M, K, 1.0, dtype, 61)
+    v, i = bs_ref.prune_pack(W, bank, k)
+    vals, idx = dev(v), dev(i)
+    for k2 in sorted({1, 2, 3, max(1, k // 2), max(1, k - 1), k} & set(range(1, k + 1))):
+        v2, i2 = bs.bs_reprune(vals, idx, bank, k2)
+        v_ref, i_ref = bs_ref.reprune(v, i, k2)
+        assert host(v2).tobytes() == v_ref.tobytes(), (k2,)
+        assert host(i2).tobytes() == i_ref.tobytes(), (k2,)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_reprune_ties(dtype):
+    W = workloads.tie_heavy_weights(33, 512, 3, dtype, 62)
+    for bank, k, k2 in [(64, 24, 8), (128, 40, 13), (32, 32, 5), (256, 100, 31)]:
+        v, i = bs_ref.prune_pack(W, bank, k)
+        v2, i2 = bs.bs_reprune(dev(v), dev(i), bank, k2)
+        v_ref, i_ref = bs_ref.reprune(v, i, k2)
+        assert host(v2).tobytes() == v_ref.tobytes() and host(i2).tobytes() == i_ref.tobytes()
+
+
+@pytest.mark.parametrize("name,k2", [("lstm1500", 5), ("sweep_k32", 8), ("fc6_b1", 3)])
+def test_reprune_full_size(name, k2):
+    """At full size the re-pruned matrix must be what pruning W to k2 directly gives
+    (checked on the GPU's own one-shot result, itself checked against the oracle in
+    test_full_size_pack_and_spmv) and what the oracle gives on a sample of rows."""
+    say("reprune full", name, k2)
+    wl, W, _ = workloads.make(name)
+    Wd = dev(W)
+    vals, idx = bs.bs_prune_pack(Wd, wl.bank, wl.k)
+    v2, i2 = bs.bs_reprune(vals, idx, wl.bank, k2)
+    v1, i1 = bs.bs_prune_pack(Wd, wl.bank, k2)
+    assert torch.equal(v2.view(torch.uint8), v1.view(torch.uint8)) and torch.equal(i2, i1)
+    rows = np.arange(0, wl.M, 97)
+    v_ref, i_ref = bs_ref.reprune(*bs_ref.prune_pack(np.ascontiguousarray(W[rows]), wl.bank, wl.k), k2)
+    rsel = torch.from_numpy(rows).to(v2.device)
+    assert host(v2[rsel]).tobytes() == v_ref.tobytes() and host(i2[rsel]).tobytes() == i_ref.tobytes()
+
+
 FULL = ["tiny", "lstm1500", "sweep_k32", "sweep_k16", "sweep_k8", "sweep_k4", "sweep_k2",
-        "fc6_b1"]
+        "fc6_b1", "lstm1500_b25_k5", "lstm1500_b50_k15", "lstm1500_b100_k40"]
 
 
 @pytest.mark.parametrize("name", FULL)
