@@ -107,6 +107,8 @@ OTHER_WORKLOADS = ("tiny", "sweep_k32", "sweep_k16", "sweep_k8", "sweep_k4", "sw
                    "lstm1500_b25_k10", "lstm1500_b25_k5", "lstm1500_b50_k20", "lstm1500_b50_k15",
                    "lstm1500_b50_k10", "lstm1500_b100_k40", "lstm1500_b100_k30", "lstm1500_b100_k20",
                    "bilstm1024",
+                   # Sec. 4.2: convolution layers as products over im2col columns
+                   "conv5_n196", "conv4_n784", "conv2_n12544",
                    # Sec. 4.1's matrix shape, 50 % .. 97 % sparse, batch 1 and 8
                    "bench16k_k128", "bench16k_k64", "bench16k_k32", "bench16k_k16", "bench16k_k8",
                    "bench16k_k128_n8", "bench16k_k32_n8", "bench16k_k8_n8")
@@ -169,6 +171,16 @@ def quick_measure(torch, np, bs, workloads, dev, name, o_time, launches=200):
     d_us = region_us(torch, fn, n_d)
     res["dense_us"] = round(d_us, 1)
     res["speedup_vs_dense"] = round(d_us / us, 2)
+    # context: the vendor library's dense product on the same matrix (torch.matmul ->
+    # rocBLAS / hipBLASLt; fp16 weights multiply an fp16 copy of X there)
+    try:
+        Xl = Xd if wl.dtype == "f32" else Xd.half()
+        lib = lambda i: torch.matmul(Wc[i % len(Wc)], Xl)
+        for i in range(3):
+            lib(i)
+        res["dense_library_us"] = round(region_us(torch, lib, n_d), 1)
+    except Exception as exc:
+        res["dense_library_error"] = str(exc)[:80]
     # eq. (5): the dense time scaled by the kept fraction, launch overhead not scaled
     res["ideal_us_eq5"] = round(max(d_us - o_time, 0.0) * (1 - wl.sparsity) + o_time, 2)
     # pruning + packing this matrix (W rotates as for the dense baseline)

@@ -85,6 +85,11 @@ WORKLOADS = {w.name: w for w in [
     _mk(6, "bench16k_k32", 16384, 8192, 256, 32, 1.0),
     _mk(6, "bench16k_k16", 16384, 8192, 256, 16, 1.0),
     _mk(6, "bench16k_k8", 16384, 8192, 256, 8, 1.0),
+    # Sec. 4.2: convolution as a matrix product over im2col columns, VGG-16 layer shapes
+    # (Table 2): out-channels x (in-channels * 3 * 3), one column per output pixel
+    _mk(9, "conv5_n196", 512, 4608, 64, 16, 0.02, N=196),
+    _mk(9, "conv4_n784", 512, 4608, 64, 16, 0.02, N=784),
+    _mk(9, "conv2_n12544", 128, 576, 64, 16, 0.05, N=12544),
     # Table 4's axes on the LSTM gate matrix: balance range 25 / 50 / 100 at 60 % .. 80 %
     _mk(8, "lstm1500_b25_k10", 6000, 3000, 25, 10, 0.05),
     _mk(8, "lstm1500_b25_k5", 6000, 3000, 25, 5, 0.05),

@@ -216,7 +216,8 @@ def test_spmm_small(M, K, bank, k, N):
     check_spmm(W, bank, k, X, 1e-5)
 
 
-@pytest.mark.parametrize("name", ["lstm1500_n8", "lstm1500_n32", "lstm1500_n128", "fc6_b16"])
+@pytest.mark.parametrize("name", ["lstm1500_n8", "lstm1500_n32", "lstm1500_n128", "fc6_b16",
+                                  "conv5_n196", "conv4_n784", "conv2_n12544"])
 def test_spmm_full_size(name):
     say("spmm full", name)
     wl, W, X = workloads.make(name)
