@@ -179,6 +179,7 @@ def quick_measure(torch, np, bs, workloads, dev, name, o_time, launches=200):
         for i in range(3):
             lib(i)
         res["dense_library_us"] = round(region_us(torch, lib, n_d), 1)
+        res["speedup_vs_faster_dense"] = round(min(d_us, res["dense_library_us"]) / us, 2)
     except Exception as exc:
         res["dense_library_error"] = str(exc)[:80]
     # eq. (5): the dense time scaled by the kept fraction, launch overhead not scaled
