@@ -312,14 +312,22 @@ def bs_lstm_sequence(vals, idx, bank: int, X, h0, bias, c, H_all=None):
     return H_all
 
 
-def bs_reprune(vals, idx, bank: int, k2: int):
-    """Packed [M, K/bank, k] -> packed [M, K/bank, k2], k2 <= k: (vals2, idx2)."""
+def bs_reprune(vals, idx, bank: int, k2: int, out=None):
+    """Packed [M, K/bank, k] -> packed [M, K/bank, k2], k2 <= k: (vals2, idx2);
+    `out` = (vals2, idx2) to write into existing tensors."""
     code, M, K, k = _packed(vals, idx, bank)
     if k2 < 1 or k2 > k:
         raise BsError(2, "bs_reprune")
     nb = K // bank
-    vals2 = torch.empty((M, nb, k2), dtype=vals.dtype, device=vals.device)
-    idx2 = torch.empty((M, nb, k2), dtype=torch.uint8, device=vals.device)
+    if out is None:
+        vals2 = torch.empty((M, nb, k2), dtype=vals.dtype, device=vals.device)
+        idx2 = torch.empty((M, nb, k2), dtype=torch.uint8, device=vals.device)
+    else:
+        vals2, idx2 = out
+        _dev(vals2, "vals2", vals.dtype)
+        _dev(idx2, "idx2", torch.uint8)
+        if tuple(vals2.shape) != (M, nb, k2) or tuple(idx2.shape) != (M, nb, k2):
+            raise ValueError(f"out must be two [{M}, {nb}, {k2}] tensors")
     _check(load_library().bs_reprune(_ptr(vals), _ptr(idx), code, M, K, bank, k, k2, _ptr(vals2),
                                      _ptr(idx2), _stream()), "bs_reprune")
     return vals2, idx2
