@@ -11,20 +11,24 @@
 //     columns of X (sb*B rows of nl*4 floats) is copied into LDS with
 //     direct-to-LDS loads; a workgroup owns one tile and a range of rows;
 //   * within a wavefront LPR lanes share a (row, column group) and walk the
-//     row's entries of the slab in 16-byte value chunks, nl column groups of
-//     4*Q columns sit side by side, and the remaining lanes take further rows;
+//     row's entries of the slab in 16-byte value chunks; the nl column groups of
+//     4*Q columns are neighbouring lanes (the nl lanes that gather one entry read
+//     adjacent bytes of one LDS row: half the bank-conflict cycles of the other
+//     order), and the remaining lanes take further rows;
 //     an entry costs one address computation, Q 16-byte LDS reads and 4*Q
 //     multiply-adds per lane;
 //   * the LDS address of an entry comes from a per-workgroup table
 //     (position in the slab -> byte offset of its bank's rows), as in SpMV;
 //   * the chunks of the next row pass are loaded while the current pass is
 //     consumed (two register sets);
-//   * the LPR partial sums are combined with DPP moves; with more than one slab
+//   * the LPR partial sums (nl lanes apart) are combined with lane exchanges; with more than one slab
 //     the slab results go to a workspace and a second kernel adds them in slab
 //     order, so results do not depend on scheduling;
 //   * workgroups that share a tile get consecutive numbers after an XCD-aware
 //     remap, so the tile of X is fetched into one XCD's L2.
 #pragma once
+#include <type_traits>
+
 #include "bs_internal.h"
 
 namespace bs {
@@ -74,9 +78,14 @@ __device__ __forceinline__ void spmm_consume(const char* xcol, const uint32_t* t
         // round_base = c0 - l is the same for every lane: a slot that lies past the
         // end of the run for all of them is skipped by a scalar branch
         if (round_base + u * LPR >= cps) break;
-        const int c = c0 + u * LPR;
-        const bool ok = c < cps;
-        const uint32_t* t = tab + (ok ? c : 0) * CH;
+        // Lanes past the end of the run hold a re-read of the run's last chunk; they
+        // gather that chunk's own rows of X (operands this matrix row uses anyway) and
+        // multiply them by zero.  Slots that are full for every lane (a scalar test)
+        // skip the selects.
+        const bool all_in = round_base + (u + 1) * LPR <= cps;
+        const int c = min(c0 + u * LPR, cps - 1);
+        const bool ok = c0 + u * LPR < cps;
+        const uint32_t* t = tab + c * CH;
         uint32_t base[CH];
         if constexpr (CH >= 4) {
 #pragma unroll
@@ -90,26 +99,24 @@ __device__ __forceinline__ void spmm_consume(const char* xcol, const uint32_t* t
         } else {
             base[0] = t[0];
         }
-        // sums of this slot alone, so that a masked slot (which gathers real X values
-        // through a re-read chunk) can be dropped whole, whatever those values are
-        float p[4 * Q];
+        auto entries = [&](auto masked) {
 #pragma unroll
-        for (int n = 0; n < 4 * Q; ++n) p[n] = 0.f;
+            for (int i = 0; i < CH; ++i) {
+                float w = value_at<VT>(v[u], i);
+                if constexpr (decltype(masked)::value) w = ok ? w : 0.f;
+                const char* row = xcol + base[i] + __umul24(offset_at(o[u], i), pitch);
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const float w = value_at<VT>(v[u], i);
-            const char* row = xcol + base[i] + __umul24(offset_at(o[u], i), pitch);
-#pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                const float4 xv = *reinterpret_cast<const float4*>(row + q * 16);
-                p[4 * q + 0] = fmaf(w, xv.x, p[4 * q + 0]);
-                p[4 * q + 1] = fmaf(w, xv.y, p[4 * q + 1]);
-                p[4 * q + 2] = fmaf(w, xv.z, p[4 * q + 2]);
-                p[4 * q + 3] = fmaf(w, xv.w, p[4 * q + 3]);
+                for (int q = 0; q < Q; ++q) {
+                    const float4 xv = *reinterpret_cast<const float4*>(row + q * 16);
+                    acc[4 * q + 0] = fmaf(w, xv.x, acc[4 * q + 0]);
+                    acc[4 * q + 1] = fmaf(w, xv.y, acc[4 * q + 1]);
+                    acc[4 * q + 2] = fmaf(w, xv.z, acc[4 * q + 2]);
+                    acc[4 * q + 3] = fmaf(w, xv.w, acc[4 * q + 3]);
+                }
             }
-        }
-#pragma unroll
-        for (int n = 0; n < 4 * Q; ++n) acc[n] += ok ? p[n] : 0.f;
+        };
+        if (all_in) entries(std::false_type{});
+        else entries(std::true_type{});
     }
 }
 
@@ -140,8 +147,10 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
     const int cps = seg / CH;                     // exact by construction of the plan
 
     // lane -> (row slot, column group, lane in the chunk walk)
-    const int l = tid % LPR;
-    const int cg = (tid / LPR) % nl;
+    // column groups run fastest: the nl lanes that gather one entry read nl*16 adjacent
+    // bytes of one LDS row
+    const int cg = tid % nl;
+    const int l = (tid / nl) % LPR;
     const int slot = tid / (LPR * nl);
     const int rows_per_pass = nthr / (LPR * nl);
     const int r_begin = g * a.rows_per_wg;
@@ -233,8 +242,12 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
                 spmm_consume<VT, CH, LPR, U, Q>(xcol, tab, pitch, vt, ot, c0, c0 - l, cps, acc);
             }
         }
+        // the LPR lanes of a (row, column group) are nl lanes apart
 #pragma unroll
-        for (int n = 0; n < 4 * Q; ++n) acc[n] = group_sum<LPR>(acc[n]);
+        for (int step = 1; step < LPR; step <<= 1) {
+#pragma unroll
+            for (int n = 0; n < 4 * Q; ++n) acc[n] += __shfl_xor(acc[n], step * nl, kWave);
+        }
         if (l == 0 && row < r_end) {
             float* dst = outp + (size_t)row * a.ld_out + n0 + cg * (4 * Q);
 #pragma unroll
