@@ -95,6 +95,21 @@ def _dev(t: torch.Tensor, what: str, dtype=None) -> torch.Tensor:
     return t
 
 
+def _rows(t: torch.Tensor, what: str) -> int:
+    """A 2-D fp32 GPU tensor whose rows are contiguous (a column slice of a wider
+    row-major tensor is fine): returns its leading dimension in elements."""
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{what} must be a tensor on the GPU")
+    if t.dtype != torch.float32 or t.dim() != 2:
+        raise TypeError(f"{what} must be a 2-D float32 tensor")
+    if t.shape[1] > 1 and t.stride(1) != 1:
+        raise ValueError(f"{what}: elements of a row must be adjacent")
+    ld = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], 1)
+    if ld < t.shape[1]:
+        raise ValueError(f"{what}: rows overlap")
+    return ld
+
+
 def _stream() -> ctypes.c_void_p:
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -212,16 +227,18 @@ def bs_spmv_ex(vals, idx, bank, x, lanes_per_row, rows_per_wg, out=None, start_e
 
 
 def bs_spmm(vals, idx, bank: int, X, out=None, workspace=None):
-    """Y [M, N] = W_sparse . X, X [K, N] fp32 row-major on the GPU.  `workspace`
-    is an optional uint8 tensor of at least bs_spmm_workspace_bytes(...) bytes;
-    without it one is taken from torch's allocator for this call."""
+    """Y [M, N] = W_sparse . X, X [K, N] fp32 on the GPU, rows contiguous (X and `out`
+    may be column slices of wider row-major tensors: their row strides are passed as
+    leading dimensions).  `workspace` is an optional uint8 tensor of at least
+    bs_spmm_workspace_bytes(...) bytes; without it one is taken from torch's allocator
+    for this call."""
     code, M, K, k = _packed(vals, idx, bank)
-    _dev(X, "X", torch.float32)
-    if X.dim() != 2 or X.shape[0] != K:
+    ldx = _rows(X, "X")
+    if X.shape[0] != K:
         raise ValueError(f"X must be [{K}, N]")
     N = X.shape[1]
-    Y = torch.empty((M, N), dtype=torch.float32, device=vals.device) if out is None else _dev(
-        out, "out", torch.float32)
+    Y = torch.empty((M, N), dtype=torch.float32, device=vals.device) if out is None else out
+    ldy = _rows(Y, "out")
     if tuple(Y.shape) != (M, N):
         raise ValueError(f"out must be [{M}, {N}]")
     lib = load_library()
@@ -229,7 +246,7 @@ def bs_spmm(vals, idx, bank: int, X, out=None, workspace=None):
     if need and workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=vals.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib.bs_spmm(_ptr(vals), _ptr(idx), code, M, K, bank, k, _ptr(X), N, N, _ptr(Y), N,
+    _check(lib.bs_spmm(_ptr(vals), _ptr(idx), code, M, K, bank, k, _ptr(X), N, ldx, _ptr(Y), ldy,
                        _ptr(workspace), ws_bytes, _stream()), "bs_spmm")
     return Y
 

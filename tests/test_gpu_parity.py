@@ -254,6 +254,30 @@ def test_benchmark_shape_sampled_rows(name):
     assert err <= TOL[wl.dtype]
 
 
+@pytest.mark.parametrize("N,ldx,ldy,col0", [(8, 12, 24, 4), (33, 40, 37, 0), (64, 68, 64, 4),
+                                            (5, 7, 9, 0), (130, 136, 132, 0), (16, 21, 16, 4)])
+def test_spmm_leading_dimensions(N, ldx, ldy, col0):
+    """X and Y as column slices of wider row-major buffers (ldx, ldy > N): the product
+    reads only its N columns and writes only its N columns."""
+    M, K, bank, k = 70, 600, 100, 10
+    W = workloads.draw_weights(M, K, 0.05, "f32", 71)
+    v, i = bs_ref.prune_pack(W, bank, k)
+    X = workloads.draw_activations(K, N, 71).reshape(K, N)
+    Xw = torch.full((K, ldx + col0), float("nan"), device=DEV)      # poison around the slice
+    Xs = Xw[:, col0:col0 + N]
+    Xs.copy_(dev(X))
+    Yw = torch.full((M, ldy), -7.0, device=DEV)
+    Ys = Yw[:, :N]
+    bs.bs_spmm(dev(v), dev(i), bank, Xs, out=Ys)
+    Y = host(Ys.contiguous())
+    assert bs_ref.rel_l2(Y, bs_ref.spmm(v, i, bank, X)) <= 1e-5
+    assert bool((Yw[:, N:] == -7.0).all())                           # padding untouched
+    if ldx > N + 1:   # a slice that does not start on a 16-byte boundary is refused
+        with pytest.raises(bs.BsError) as e:
+            bs.bs_spmm(dev(v), dev(i), bank, Xw[:, 1:1 + N], out=Ys)
+        assert e.value.status == 4
+
+
 def test_spmm_n1_matches_spmv_and_f16_small():
     wl, W, x = workloads.make("tiny")
     v, i = bs_ref.prune_pack(W, wl.bank, wl.k)
