@@ -67,6 +67,137 @@ __global__ __launch_bounds__(256) void dense_gemv_kernel(const VT* __restrict__ 
     }
 }
 
+// ---- GEMM for a few columns (used for N <= 8): bound by streaming W once ---
+// The workgroup keeps a slab of X in LDS, transposed (NC columns x KS rows, zero
+// padded, pitch KS + 4 so that neither the staging writes nor the reads below
+// conflict); a wavefront owns R rows of W and its lanes walk them in 16-byte pieces,
+// P pieces per lane and slab, all loaded before the slab of X is staged so that they
+// fly meanwhile.  A piece (E consecutive k) meets, per column, E consecutive floats of
+// the transposed slab: neighbouring lanes read neighbouring 16 bytes.  A lane keeps
+// R*NC sums, combined across the wavefront at the end.
+template <typename VT, int NC, int R, int P>
+__global__ __launch_bounds__(1024) void dense_gemm_stream(const VT* __restrict__ W,
+                                                          const float* __restrict__ X,
+                                                          float* __restrict__ Y, int M, int K, int N,
+                                                          int64_t ldx, int64_t ldy) {
+    constexpr int E = Vec16<VT>::n;            // weights per 16-byte piece
+    constexpr int KS = kWave * E * P;          // rows of X per slab
+    constexpr int KSP = KS + 4;                // LDS pitch of one column
+    extern __shared__ __align__(16) float xs_dense[];   // [NC][KSP]
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6, n_waves = nthr >> 6;
+    const int row0 = (blockIdx.x * n_waves + wave) * R;
+
+    float acc[R][NC];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int n = 0; n < NC; ++n) acc[r][n] = 0.f;
+
+    // this wavefront's pieces of a slab: rows past M re-read the last row, pieces past K
+    // re-read the row's last piece and count nothing
+    auto load_slab = [&](int k_base, uint4 (&raw)[R][P]) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const VT* wrow = W + (size_t)min(row0 + r, M - 1) * K;
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                const int k0 = min(k_base + (p * kWave + lane) * E, K - E);
+                raw[r][p] = *reinterpret_cast<const uint4*>(wrow + k0);
+            }
+        }
+    };
+    auto use_slab = [&](int k_base, const uint4 (&raw)[R][P]) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const int kr0 = (p * kWave + lane) * E;
+            const bool live = k_base + kr0 < K;
+            float w[R][E];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                VT wv[E];
+                __builtin_memcpy(wv, &raw[r][p], 16);
+#pragma unroll
+                for (int e = 0; e < E; ++e) w[r][e] = live ? to_f32<VT>(wv[e]) : 0.f;
+            }
+#pragma unroll
+            for (int n = 0; n < NC; ++n) {
+#pragma unroll
+                for (int h = 0; h < E / 4; ++h) {
+                    const float4 x =
+                        *reinterpret_cast<const float4*>(xs_dense + n * KSP + kr0 + 4 * h);
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        acc[r][n] = fmaf(w[r][4 * h + 0], x.x, acc[r][n]);
+                        acc[r][n] = fmaf(w[r][4 * h + 1], x.y, acc[r][n]);
+                        acc[r][n] = fmaf(w[r][4 * h + 2], x.z, acc[r][n]);
+                        acc[r][n] = fmaf(w[r][4 * h + 3], x.w, acc[r][n]);
+                    }
+                }
+            }
+        }
+    };
+    auto stage_slab = [&](int k_base) {
+        for (int i = tid; i < KS * NC; i += nthr) {
+            const int kr = i / NC, n = i - kr * NC;      // neighbouring threads: one row of X
+            const int k = k_base + kr;
+            xs_dense[n * KSP + kr] = (k < K && n < N) ? X[(size_t)k * ldx + n] : 0.f;
+        }
+    };
+
+    // two register sets: the next slab's pieces of W are in flight while this one is used
+    uint4 rawA[R][P], rawB[R][P];
+    load_slab(0, rawA);
+    for (int k_base = 0; k_base < K; k_base += 2 * KS) {
+        if (k_base) __syncthreads();           // everyone is done with the previous slab of X
+        stage_slab(k_base);
+        __syncthreads();
+        if (k_base + KS < K) load_slab(k_base + KS, rawB);
+        use_slab(k_base, rawA);
+        if (k_base + KS >= K) break;
+        __syncthreads();
+        stage_slab(k_base + KS);
+        __syncthreads();
+        if (k_base + 2 * KS < K) load_slab(k_base + 2 * KS, rawA);
+        use_slab(k_base + KS, rawB);
+    }
+
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+#pragma unroll
+        for (int n = 0; n < NC; ++n) {
+            const float sum = group_sum<kWave>(acc[r][n]);
+            if (lane == 0 && row0 + r < M && n < N) Y[(size_t)(row0 + r) * ldy + n] = sum;
+        }
+    }
+}
+
+template <typename VT, int NC, int P>
+int gemm_stream_launch(const VT* w, int64_t M, int64_t K, const float* X, int64_t N, int64_t ldx,
+                       float* Y, int64_t ldy, hipStream_t st) {
+    constexpr int R = 2;
+    constexpr int KS = kWave * Vec16<VT>::n * P;
+    const int threads = M >= 2048 ? 1024 : 256;    // fewer copies of X per row for tall matrices
+    const int rows_per_wg = threads / kWave * R;
+    const int64_t grid = (M + rows_per_wg - 1) / rows_per_wg;
+    const size_t lds = (size_t)(KS + 4) * NC * sizeof(float);
+    auto kern = dense_gemm_stream<VT, NC, R, P>;
+    if (lds > 48 * 1024) {
+        static bool raised = false;
+        if (!raised) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kMaxLdsBytes) != hipSuccess)
+                return BS_ERR_HIP;
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(threads), lds, st, w, X, Y, (int)M, (int)K,
+                       (int)N, ldx, ldy);
+    return hip_status(hipGetLastError());
+}
+
 // ---- GEMM without matrix cores (rows not 16-byte aligned): 64 x BN output tile
 //      per workgroup, K in steps of 32 through LDS ------------------------------
 constexpr int BM = 64, BK = 32;
@@ -281,6 +412,11 @@ template <typename VT>
 int gemm_t(const void* W, int64_t M, int64_t K, const float* X, int64_t N, int64_t ldx, float* Y,
            int64_t ldy, hipStream_t st) {
     const VT* w = static_cast<const VT*>(W);
+    if (N <= 8 && K % Vec16<VT>::n == 0 && K >= Vec16<VT>::n) {
+        // up to 8 columns: stream W once, 32 KB of X (1024 rows) per slab.  (With 16 or 32
+        // columns this kernel measured slower than the matrix-core kernel below.)
+        return gemm_stream_launch<VT, 8, 16 / Vec16<VT>::n>(w, M, K, X, N, ldx, Y, ldy, st);
+    }
     if (K % 8 == 0) {   // rows start on 16-byte boundaries: the matrix-core kernel
         if (N <= 32) return gemm_mfma_launch<VT, 1, 16, 16>(w, M, K, X, N, ldx, Y, ldy, st);
         return gemm_mfma_launch<VT, 2, 32, 8>(w, M, K, X, N, ldx, Y, ldy, st);
