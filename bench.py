@@ -404,6 +404,48 @@ def main():
                                            (wl.val_bytes + 1) / r_us / 1e3, 1)
         ev.close()
 
+        # the machine's floor, measured with the library's two helper kernels in the same
+        # protocol (a graph of launches): an empty launch, a kernel that only reads this
+        # workload's bytes (cold, rotating buffers), and a large streaming read
+        try:
+            def graph_us(launch, n):
+                side2 = torch.cuda.Stream()
+                with torch.cuda.stream(side2):
+                    for i in range(min(n, 8)):
+                        launch(i)
+                torch.cuda.synchronize()
+                gp = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gp):
+                    for i in range(n):
+                        launch(i)
+                gp.replay()
+                torch.cuda.synchronize()
+                return region_us(torch, lambda i: gp.replay(), 3) / n
+
+            floor = {}
+            floor["empty_launch_us"] = round(graph_us(lambda i: bs.bs_probe_empty(750, 256), 1000), 3)
+            same = (alg_bytes + 15) // 16 * 16
+            n_same = max(2, -(-2 * LLC_BYTES // same) + 1)
+            bufs = [torch.empty(same, dtype=torch.uint8, device=dev) for _ in range(n_same)]
+            for b_ in bufs:
+                b_.fill_(1)
+            t_same = graph_us(lambda i: bs.bs_probe_stream_read(bufs[i % n_same]), 2 * n_same)
+            floor["stream_read_same_bytes_us"] = round(t_same, 3)
+            floor["stream_read_same_bytes_GBps"] = round(same / t_same / 1e3, 1)
+            del bufs
+            big = 288 << 20
+            bufs = [torch.empty(big, dtype=torch.uint8, device=dev) for _ in range(3)]
+            for b_ in bufs:
+                b_.fill_(1)
+            t_big = graph_us(lambda i: bs.bs_probe_stream_read(bufs[i % 3]), 12)
+            floor["stream_read_288MB_us"] = round(t_big, 2)
+            floor["stream_read_288MB_GBps"] = round(big / t_big / 1e3, 1)
+            floor["value_over_same_bytes_stream"] = round(t_same / us_per_step, 3)
+            del bufs
+            extras["machine_floor"] = floor
+        except Exception as exc:                 # never lose the headline line
+            extras["machine_floor_error"] = str(exc)[:200]
+
         # fused LSTM time steps (Sec. 4.3's language model: H = I = 1500 is this very gate
         # matrix): T dependent steps replayed from one graph, weights cache resident as in
         # a real recurrence; per step = the sparse product + bias, gates and cell update

@@ -179,6 +179,21 @@ int bs_dense_gemv(const void* W, int dtype, int64_t M, int64_t K,
 int bs_dense_gemm(const void* W, int dtype, int64_t M, int64_t K,
                   const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy, void* stream);
 
+/* ---- measurement helpers (not part of the method) --------------------------
+ *
+ * For benchmarks that must tell a kernel's quality from the machine's floor (the
+ * products of Sec. 4 last a few microseconds on this GPU):
+ * bs_probe_empty        launches an empty kernel of `grid` workgroups of `threads`
+ *                       lanes (1..1024, a multiple of 64);
+ * bs_probe_stream_read  a kernel that only reads `bytes` bytes (a multiple of 16,
+ *                       at least 16) from DEVICE `src`, 16 bytes per lane and load, and
+ *                       stores nothing; `sink` is DEVICE memory of at least 256 bytes
+ *                       that is never written for real data (may be NULL).
+ * Both enqueue on `stream` like every other call.
+ */
+int bs_probe_empty(int grid, int threads, void* stream);
+int bs_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ BS_F32, BS_F16 = 0, 1
 EXPORTS = (
     "bs_nnz", "bs_vals_bytes", "bs_idx_bytes", "bs_status_str", "bs_prune_pack", "bs_spmv",
     "bs_spmv_ex", "bs_spmm_workspace_bytes", "bs_spmm", "bs_dense_gemv", "bs_dense_gemm",
-    "bs_lstm_step", "bs_lstm_sequence", "bs_reprune",
+    "bs_lstm_step", "bs_lstm_sequence", "bs_reprune", "bs_probe_empty", "bs_probe_stream_read",
 )
 
 
@@ -65,11 +65,14 @@ def load_library():
     lib.bs_spmm.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, i64, vp, i64, vp, sz, vp]
     lib.bs_dense_gemv.argtypes = [vp, i32, i64, i64, vp, vp, vp]
     lib.bs_dense_gemm.argtypes = [vp, i32, i64, i64, vp, i64, i64, vp, i64, vp]
+    lib.bs_probe_empty.argtypes = [i32, i32, vp]
+    lib.bs_probe_stream_read.argtypes = [vp, sz, vp, vp]
     lib.bs_reprune.argtypes = [vp, vp, i32, i64, i64, i32, i32, i32, vp, vp, vp]
     lib.bs_lstm_step.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.bs_lstm_sequence.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, vp, vp, vp, vp, vp]
     for name in ("bs_prune_pack", "bs_spmv", "bs_spmv_ex", "bs_spmm", "bs_dense_gemv",
-                 "bs_dense_gemm", "bs_lstm_step", "bs_lstm_sequence", "bs_reprune"):
+                 "bs_dense_gemm", "bs_lstm_step", "bs_lstm_sequence", "bs_reprune", "bs_probe_empty",
+                 "bs_probe_stream_read"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -348,3 +351,16 @@ def bs_reprune(vals, idx, bank: int, k2: int, out=None):
     _check(load_library().bs_reprune(_ptr(vals), _ptr(idx), code, M, K, bank, k, k2, _ptr(vals2),
                                      _ptr(idx2), _stream()), "bs_reprune")
     return vals2, idx2
+
+
+def bs_probe_empty(grid: int = 256, threads: int = 256):
+    """Measurement helper: launch an empty kernel on the current stream."""
+    _check(load_library().bs_probe_empty(grid, threads, _stream()), "bs_probe_empty")
+
+
+def bs_probe_stream_read(src: torch.Tensor, sink: torch.Tensor = None):
+    """Measurement helper: a kernel that only reads all of `src` (bytes a multiple of 16)."""
+    _dev(src, "src")
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().bs_probe_stream_read(_ptr(src), nbytes, _ptr(sink), _stream()),
+           "bs_probe_stream_read")

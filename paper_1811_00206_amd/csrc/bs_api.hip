@@ -42,6 +42,19 @@ size_t bs_vals_bytes(int64_t M, int64_t K, int bank, int k, int dtype) {
 
 size_t bs_idx_bytes(int64_t M, int64_t K, int bank, int k) { return bs_nnz(M, K, bank, k); }
 
+int bs_probe_empty(int grid, int threads, void* stream) {
+    if (grid < 1 || grid > 65536 || threads < 64 || threads > 1024 || threads % 64)
+        return BS_ERR_SHAPE;
+    return bs::launch_probe_empty(grid, threads, static_cast<hipStream_t>(stream));
+}
+
+int bs_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
+    if (!src) return BS_ERR_NULL;
+    if (bytes < 16 || bytes % 16) return BS_ERR_SHAPE;
+    if (!aligned16(src) || (sink && !aligned16(sink))) return BS_ERR_ALIGN;
+    return bs::launch_probe_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream));
+}
+
 const char* bs_status_str(int status) {
     switch (status) {
         case BS_OK: return "ok";

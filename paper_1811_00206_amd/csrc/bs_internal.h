@@ -35,6 +35,9 @@ int launch_dense_gemv(const void* W, int dtype, int64_t M, int64_t K, const floa
                       hipStream_t st);
 int launch_dense_gemm(const void* W, int dtype, int64_t M, int64_t K, const float* X, int64_t N,
                       int64_t ldx, float* Y, int64_t ldy, hipStream_t st);
+// measurement helpers (bs_probe.hip)
+int launch_probe_empty(int grid, int threads, hipStream_t st);
+int launch_probe_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? BS_OK : BS_ERR_HIP; }
 

@@ -400,6 +400,21 @@ def test_sparse_product_equals_dense_product_of_pruned_matrix_on_gpu():
 
 # ----------------------------------------------------- errors via the C-ABI
 
+def test_measurement_helpers_run_and_refuse_bad_sizes():
+    buf = torch.ones(1 << 20, dtype=torch.uint8, device=DEV)
+    bs.bs_probe_empty(4, 64)
+    bs.bs_probe_stream_read(buf)
+    bs.bs_probe_stream_read(buf[:4096], sink=torch.zeros(64, dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+    assert bool((buf == 1).all())
+    with pytest.raises(bs.BsError):
+        bs.bs_probe_stream_read(buf[:24])            # not a multiple of 16 bytes
+    with pytest.raises(bs.BsError):
+        bs.bs_probe_empty(0, 256)
+    with pytest.raises(bs.BsError):
+        bs.bs_probe_empty(4, 100)
+
+
 def test_device_side_argument_errors():
     v = torch.zeros((4, 2, 2), dtype=torch.float32, device=DEV)
     i = torch.zeros((4, 2, 2), dtype=torch.uint8, device=DEV)
