@@ -10,23 +10,24 @@ namespace {
 
 __global__ void probe_empty_kernel() {}
 
-// every lane reads 16-byte pieces, 8 in flight; the sum is stored only if it has a
+// every lane reads 16-byte pieces, U in flight; the sum is stored only if it has a
 // value the data cannot produce, so the loads cannot be dropped
+template <int U>
 __global__ __launch_bounds__(256) void probe_stream_read_kernel(const uint4* __restrict__ src,
                                                                 uint32_t* __restrict__ sink,
                                                                 size_t n16) {
     const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t nthr = (size_t)gridDim.x * blockDim.x;
     uint32_t acc = 0;
-    for (size_t i = tid; i < n16; i += 8 * nthr) {
-        uint4 v[8];
+    for (size_t i = tid; i < n16; i += U * nthr) {
+        uint4 v[U];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < U; ++u) {
             const size_t j = i + u * nthr;
             v[u] = src[j < n16 ? j : n16 - 1];
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+        for (int u = 0; u < U; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
     if (acc == 0x9e3779b9u && sink) sink[tid & 63] = acc;
 }
@@ -40,12 +41,19 @@ int launch_probe_empty(int grid, int threads, hipStream_t st) {
 
 int launch_probe_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st) {
     const size_t n16 = bytes / 16;
-    // one 16-byte piece per lane and pass of 8: enough workgroups to cover the buffer once
-    size_t grid = (n16 + 256 * 8 - 1) / (256 * 8);
-    if (grid < 1) grid = 1;
-    if (grid > 65536) grid = 65536;
-    hipLaunchKernelGGL(probe_stream_read_kernel, dim3((unsigned)grid), dim3(256), 0, st,
-                       static_cast<const uint4*>(src), static_cast<uint32_t*>(sink), n16);
+    const uint4* p = static_cast<const uint4*>(src);
+    uint32_t* s = static_cast<uint32_t*>(sink);
+    // Small buffers are read fastest by as many short-lived wavefronts as possible (one
+    // piece per lane: measured 2.9 against 3.5 us for 9 MB with 8 pieces per lane); large
+    // ones by a fixed grid with 8 pieces per lane in flight.
+    if (n16 <= (size_t)16384 * 256) {
+        size_t grid = (n16 + 255) / 256;
+        hipLaunchKernelGGL(probe_stream_read_kernel<1>, dim3((unsigned)grid), dim3(256), 0, st, p, s, n16);
+    } else {
+        size_t grid = (n16 + 256 * 8 - 1) / (256 * 8);
+        if (grid > 65536) grid = 65536;
+        hipLaunchKernelGGL(probe_stream_read_kernel<8>, dim3((unsigned)grid), dim3(256), 0, st, p, s, n16);
+    }
     return hip_status(hipGetLastError());
 }
 
