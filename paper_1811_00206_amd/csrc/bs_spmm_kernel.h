@@ -140,7 +140,8 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
     const int n0 = z * a.nt;
     const int ntw = min(a.nt, a.N - n0);          // live columns of this tile
     const int nl = a.nl;
-    const int f4_per_row = nl * Q;                // LDS row = nl groups of Q float4
+    const int f4_per_row = nl * Q;                // LDS row = nl groups of Q float4 (a power of two)
+    const int f4_shift = 31 - __builtin_clz(f4_per_row);
     const uint32_t pitch = (uint32_t)f4_per_row * 16u;   // bytes per LDS row
     const int slab_rows = banks * a.B;
     const int seg = banks * a.k;                  // entries of one row inside the slab
@@ -149,10 +150,11 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
     // lane -> (row slot, column group, lane in the chunk walk)
     // column groups run fastest: the nl lanes that gather one entry read nl*16 adjacent
     // bytes of one LDS row
-    const int cg = tid % nl;
-    const int l = (tid / nl) % LPR;
-    const int slot = tid / (LPR * nl);
-    const int rows_per_pass = nthr / (LPR * nl);
+    const int nl_shift = 31 - __builtin_clz(nl);  // nl is a power of two: shifts, not divisions
+    const int cg = tid & (nl - 1);
+    const int l = (tid >> nl_shift) % LPR;
+    const int slot = (tid >> nl_shift) / LPR;
+    const int rows_per_pass = (nthr >> nl_shift) / LPR;
     const int r_begin = g * a.rows_per_wg;
     const int r_end = min(a.M, r_begin + a.rows_per_wg);
 
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
         for (int p = wave; p * 64 < total_f4; p += n_waves) {
             const int i = p * 64 + lane;
             if (i < total_f4) {
-                const int r = i / f4_per_row, c4 = i - r * f4_per_row;
+                const int r = i >> f4_shift, c4 = i & (f4_per_row - 1);
                 // columns past the tile's live width are never read back as results
                 const float* src = Xg + (size_t)r * a.ldx + min(c4 * 4, max(ntw - 4, 0));
                 __builtin_amdgcn_global_load_lds(
@@ -174,7 +176,7 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
         }
     } else {
         for (int i = tid; i < total_f4; i += nthr) {
-            const int r = i / f4_per_row, c4 = i - r * f4_per_row;
+            const int r = i >> f4_shift, c4 = i & (f4_per_row - 1);
             const float* src = Xg + (size_t)r * a.ldx + c4 * 4;
             float4 t;
             t.x = c4 * 4 + 0 < ntw ? src[0] : 0.f;
