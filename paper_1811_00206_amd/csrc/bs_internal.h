@@ -53,6 +53,13 @@ __device__ __forceinline__ uint32_t div_magic(uint32_t e, uint32_t d, uint32_t m
     return d == 1 ? e : __umulhi(e, magic);
 }
 
+// The same for any 32-bit e: the multiply-high overshoots by at most one.
+__device__ __forceinline__ uint32_t div_magic_any(uint32_t e, uint32_t d, uint32_t magic) {
+    if (d == 1) return e;
+    const uint32_t q = __umulhi(e, magic);
+    return q * d > e ? q - 1 : q;
+}
+
 // ---- cross-lane sums over aligned groups of W lanes (W = 1,2,4,...,64) -----
 // Data-parallel-primitive moves inside a 16-lane row; the two widest steps go
 // through the LDS crossbar (no LDS memory is touched).  After the call every

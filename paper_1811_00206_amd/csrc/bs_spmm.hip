@@ -124,17 +124,23 @@ SpmmPlan make_plan(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N) 
     return best;
 }
 
-// Y[r][n] = sum over slabs, in slab order
+// Y[r][n] = sum over slabs, in slab order.  magic_n = magic_u32(N): rows from element
+// numbers without a 64-bit division (M*N < 2^31 is checked by the caller).
 __global__ __launch_bounds__(256) void spmm_reduce_kernel(const float* __restrict__ P,
                                                           float* __restrict__ Y, int64_t M,
-                                                          int64_t N, int64_t ldy, int n_slabs) {
+                                                          int64_t N, int64_t ldy, int n_slabs,
+                                                          uint32_t magic_n) {
     const int64_t total = M * N;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
          i += (int64_t)gridDim.x * blockDim.x) {
         float acc = P[i];
         for (int s = 1; s < n_slabs; ++s) acc += P[(int64_t)s * total + i];
-        int64_t r = i / N, n = i - r * N;
-        Y[r * ldy + n] = acc;
+        if (ldy == N) {
+            Y[i] = acc;
+        } else {
+            const uint32_t r = div_magic_any((uint32_t)i, (uint32_t)N, magic_n);
+            Y[(int64_t)r * ldy + ((uint32_t)i - r * (uint32_t)N)] = acc;
+        }
     }
 }
 
@@ -152,6 +158,7 @@ int launch_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int6
     const SpmmPlan p = make_plan(dtype, M, K, bank, k, N);
     if (!p.ok || p.lds_bytes > (size_t)kMaxLdsBytes) return BS_ERR_UNSUPPORTED;
     if (p.ws_bytes) {
+        if (M * N > (int64_t)UINT32_MAX) return BS_ERR_UNSUPPORTED;   // the reduce kernel's 32-bit rows
         if (!workspace || workspace_bytes < p.ws_bytes) return BS_ERR_WORKSPACE;
         if ((uintptr_t)workspace % 16) return BS_ERR_ALIGN;
     }
@@ -171,6 +178,8 @@ int launch_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int6
     a.wgs_per_xcd = (int)((total + kXcds - 1) / kXcds);
     a.table_off = p.table_off;
     a.magic_k = magic_u32((uint32_t)k);
+    a.magic_rg = magic_u32((uint32_t)p.row_groups);
+    a.magic_rgs = magic_u32((uint32_t)(p.row_groups * p.n_slabs));
     // 16-byte direct-to-LDS copies need 16-byte aligned row pieces and whole groups of 4 columns
     a.dma = (N % 4 == 0 && ldx % 4 == 0) ? 1 : 0;
 
@@ -183,7 +192,8 @@ int launch_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int6
         int64_t grid = (tot + 255) / 256;
         if (grid > 256 * 16) grid = 256 * 16;
         hipLaunchKernelGGL(spmm_reduce_kernel, dim3((unsigned)grid), dim3(256), 0, st,
-                           static_cast<const float*>(workspace), Y, M, N, ldy, p.n_slabs);
+                           static_cast<const float*>(workspace), Y, M, N, ldy, p.n_slabs,
+                           magic_u32((uint32_t)N));
         return hip_status(hipGetLastError());
     }
     return BS_OK;

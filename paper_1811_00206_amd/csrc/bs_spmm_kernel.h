@@ -52,6 +52,7 @@ struct SpmmArgs {
     int total_wgs, wgs_per_xcd;
     int table_off;         // float index in LDS of the position table
     uint32_t magic_k;
+    uint32_t magic_rg, magic_rgs;   // magic_u32(row_groups), magic_u32(row_groups * n_slabs)
     int dma;               // tile rows can be copied with 16-byte direct-to-LDS loads
 };
 
@@ -130,9 +131,12 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
     const int b = blockIdx.x;
     const int wg = (b % kXcds) * a.wgs_per_xcd + b / kXcds;
     if (wg >= a.total_wgs) return;
-    const int g = wg % a.row_groups;
-    const int s = (wg / a.row_groups) % a.n_slabs;
-    const int z = wg / (a.row_groups * a.n_slabs);
+    // multiply-high by host-made reciprocals: run-time divisions cost ~30 instructions each
+    const uint32_t rgs = (uint32_t)(a.row_groups * a.n_slabs);
+    const int z = (int)div_magic_any((uint32_t)wg, rgs, a.magic_rgs);
+    const uint32_t in_tile = (uint32_t)wg - (uint32_t)z * rgs;
+    const int s = (int)div_magic_any(in_tile, (uint32_t)a.row_groups, a.magic_rg);
+    const int g = (int)(in_tile - (uint32_t)s * (uint32_t)a.row_groups);
 
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int j0 = s * a.sb;
