@@ -166,17 +166,20 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
     const float* Xg = a.X + (size_t)j0 * a.B * a.ldx + n0;
     const int total_f4 = slab_rows * f4_per_row;
     if (a.dma) {
-        const int wave = tid >> 6, lane = tid & 63, n_waves = nthr >> 6;
-        for (int p = wave; p * 64 < total_f4; p += n_waves) {
-            const int i = p * 64 + lane;
-            if (i < total_f4) {
-                const int r = i >> f4_shift, c4 = i & (f4_per_row - 1);
-                // columns past the tile's live width are never read back as results
-                const float* src = Xg + (size_t)r * a.ldx + min(c4 * 4, max(ntw - 4, 0));
+        // A lane's pieces are nthr float4 apart: the same column group every time and a
+        // constant number of rows further on (f4_per_row is a power of two <= 64), so the
+        // source address advances by a constant.
+        const int wave = tid >> 6, n_waves = nthr >> 6;
+        const int c4 = tid & (f4_per_row - 1);
+        // columns past the tile's live width are never read back as results
+        const float* src = Xg + (size_t)(tid >> f4_shift) * a.ldx + min(c4 * 4, max(ntw - 4, 0));
+        const size_t src_step = (size_t)(nthr >> f4_shift) * a.ldx;
+        int i = tid;
+        for (int p = wave; p * 64 < total_f4; p += n_waves, i += nthr, src += src_step) {
+            if (i < total_f4)
                 __builtin_amdgcn_global_load_lds(
                     (const __attribute__((address_space(1))) void*)src,
                     (__attribute__((address_space(3))) void*)(Xs + p * 256), 16, 0, 0);
-            }
         }
     } else {
         for (int i = tid; i < total_f4; i += nthr) {
