@@ -67,58 +67,78 @@ int spmm_launch_f16(int ch, int lpr, int u, int q, const SpmmArgs& a, const Spmm
 
 #ifdef __HIPCC__
 
+// One chunk slot: CH entries, each one 16-byte gather per Q and 4*Q multiply-adds.
+// MASKED: lanes past the end of the run hold a re-read of the run's last chunk; they
+// gather that chunk's own rows of X (operands this matrix row uses anyway) and
+// multiply them by zero.
+template <typename VT, int CH, int Q, bool MASKED, typename VRaw, typename IRaw>
+__device__ __forceinline__ void spmm_slot(const char* xcol, const uint32_t* tab, uint32_t pitch,
+                                          const VRaw& v, const IRaw& o, int c, int cps,
+                                          float (&acc)[4 * Q]) {
+    const bool ok = c < cps;
+    const uint32_t* t = tab + min(c, cps - 1) * CH;
+    uint32_t base[CH];
+    if constexpr (CH >= 4) {
+#pragma unroll
+        for (int q = 0; q < CH / 4; ++q) {
+            const uint4 w = reinterpret_cast<const uint4*>(t)[q];
+            base[4 * q] = w.x; base[4 * q + 1] = w.y; base[4 * q + 2] = w.z; base[4 * q + 3] = w.w;
+        }
+    } else if constexpr (CH == 2) {
+        const uint2 w = *reinterpret_cast<const uint2*>(t);
+        base[0] = w.x; base[1] = w.y;
+    } else {
+        base[0] = t[0];
+    }
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+        float w = value_at<VT>(v, i);
+        if constexpr (MASKED) w = ok ? w : 0.f;
+        const char* row = xcol + base[i] + __umul24(offset_at(o, i), pitch);
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const float4 xv = *reinterpret_cast<const float4*>(row + q * 16);
+            acc[4 * q + 0] = fmaf(w, xv.x, acc[4 * q + 0]);
+            acc[4 * q + 1] = fmaf(w, xv.y, acc[4 * q + 1]);
+            acc[4 * q + 2] = fmaf(w, xv.z, acc[4 * q + 2]);
+            acc[4 * q + 3] = fmaf(w, xv.w, acc[4 * q + 3]);
+        }
+    }
+}
+
+// NL live slots: the first NL-1 are full for every lane, the last one may be ragged
+template <typename VT, int CH, int LPR, int U, int Q, int NL, typename VRaw, typename IRaw>
+__device__ __forceinline__ void spmm_slots(const char* xcol, const uint32_t* tab, uint32_t pitch,
+                                           const VRaw (&v)[U], const IRaw (&o)[U], int c0, bool ragged,
+                                           int cps, float (&acc)[4 * Q]) {
+#pragma unroll
+    for (int u = 0; u < NL - 1; ++u)
+        spmm_slot<VT, CH, Q, false>(xcol, tab, pitch, v[u], o[u], c0 + u * LPR, cps, acc);
+    if (ragged)
+        spmm_slot<VT, CH, Q, true>(xcol, tab, pitch, v[NL - 1], o[NL - 1], c0 + (NL - 1) * LPR, cps, acc);
+    else
+        spmm_slot<VT, CH, Q, false>(xcol, tab, pitch, v[NL - 1], o[NL - 1], c0 + (NL - 1) * LPR, cps, acc);
+}
+
 // 4*Q column sums over the U chunk slots a lane holds; slot u is chunk c0 + u*LPR
 // of the row's run inside the slab (`cps` chunks).  xcol points at the lane's
-// columns of LDS row 0; pitch = bytes per LDS row.
+// columns of LDS row 0; pitch = bytes per LDS row.  round_base = c0 - l is the same for
+// every lane, so how many slots are live and whether the last one is ragged are scalar
+// decisions taken once: each case is one straight run of gathers and multiply-adds.
 template <typename VT, int CH, int LPR, int U, int Q, typename VRaw, typename IRaw>
 __device__ __forceinline__ void spmm_consume(const char* xcol, const uint32_t* tab, uint32_t pitch,
                                              const VRaw (&v)[U], const IRaw (&o)[U], int c0,
                                              int round_base, int cps, float (&acc)[4 * Q]) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        // round_base = c0 - l is the same for every lane: a slot that lies past the
-        // end of the run for all of them is skipped by a scalar branch
-        if (round_base + u * LPR >= cps) break;
-        // Lanes past the end of the run hold a re-read of the run's last chunk; they
-        // gather that chunk's own rows of X (operands this matrix row uses anyway) and
-        // multiply them by zero.  Slots that are full for every lane (a scalar test)
-        // skip the selects.
-        const bool all_in = round_base + (u + 1) * LPR <= cps;
-        const int c = min(c0 + u * LPR, cps - 1);
-        const bool ok = c0 + u * LPR < cps;
-        const uint32_t* t = tab + c * CH;
-        uint32_t base[CH];
-        if constexpr (CH >= 4) {
-#pragma unroll
-            for (int q = 0; q < CH / 4; ++q) {
-                const uint4 w = reinterpret_cast<const uint4*>(t)[q];
-                base[4 * q] = w.x; base[4 * q + 1] = w.y; base[4 * q + 2] = w.z; base[4 * q + 3] = w.w;
-            }
-        } else if constexpr (CH == 2) {
-            const uint2 w = *reinterpret_cast<const uint2*>(t);
-            base[0] = w.x; base[1] = w.y;
-        } else {
-            base[0] = t[0];
-        }
-        auto entries = [&](auto masked) {
-#pragma unroll
-            for (int i = 0; i < CH; ++i) {
-                float w = value_at<VT>(v[u], i);
-                if constexpr (decltype(masked)::value) w = ok ? w : 0.f;
-                const char* row = xcol + base[i] + __umul24(offset_at(o[u], i), pitch);
-#pragma unroll
-                for (int q = 0; q < Q; ++q) {
-                    const float4 xv = *reinterpret_cast<const float4*>(row + q * 16);
-                    acc[4 * q + 0] = fmaf(w, xv.x, acc[4 * q + 0]);
-                    acc[4 * q + 1] = fmaf(w, xv.y, acc[4 * q + 1]);
-                    acc[4 * q + 2] = fmaf(w, xv.z, acc[4 * q + 2]);
-                    acc[4 * q + 3] = fmaf(w, xv.w, acc[4 * q + 3]);
-                }
-            }
-        };
-        if (all_in) entries(std::false_type{});
-        else entries(std::true_type{});
+    static_assert(U == 2 || U == 4, "cases below");
+    const int left = cps - round_base;                    // chunks of the run from this round on
+    const int live = left >= U * LPR ? U : (left + LPR - 1) / LPR;
+    const bool ragged = left < live * LPR;
+    if constexpr (U == 4) {
+        if (live == 4) return spmm_slots<VT, CH, LPR, U, Q, 4>(xcol, tab, pitch, v, o, c0, ragged, cps, acc);
+        if (live == 3) return spmm_slots<VT, CH, LPR, U, Q, 3>(xcol, tab, pitch, v, o, c0, ragged, cps, acc);
     }
+    if (live == 2) return spmm_slots<VT, CH, LPR, U, Q, 2>(xcol, tab, pitch, v, o, c0, ragged, cps, acc);
+    if (live == 1) return spmm_slots<VT, CH, LPR, U, Q, 1>(xcol, tab, pitch, v, o, c0, ragged, cps, acc);
 }
 
 template <typename VT, int CH, int LPR, int U, int Q>
