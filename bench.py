@@ -197,7 +197,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 "
-              "(the path shards by rows, see DESIGN.md, but no multi-GPU code exists)",
+              "(the path would shard by rows, but no multi-GPU code exists)",
               file=sys.stderr)
         return 2
 
