@@ -19,8 +19,9 @@
 //     multiply-adds per lane;
 //   * the LDS address of an entry comes from a per-workgroup table
 //     (position in the slab -> byte offset of its bank's rows), as in SpMV;
-//   * the chunks of the next row pass are loaded while the current pass is
-//     consumed (two register sets);
+//   * a row's run is walked in rounds of U*LPR chunks; the chunks of the next round (of
+//     this row or of the lane's next row) are loaded while the current one is consumed
+//     (two register sets: one receives loads, the other is a copy);
 //   * the LPR partial sums (nl lanes apart) are combined with lane exchanges; with more than one slab
 //     the slab results go to a workspace and a second kernel adds them in slab
 //     order, so results do not depend on scheduling;
@@ -54,6 +55,9 @@ struct SpmmArgs {
     uint32_t magic_k;
     uint32_t magic_rg, magic_rgs;   // magic_u32(row_groups), magic_u32(row_groups * n_slabs)
     int dma;               // tile rows can be copied with 16-byte direct-to-LDS loads
+    int n_passes;          // row passes of a workgroup: ceil(rows_per_wg / rows per pass)
+    // one lane per (row, column group) (bs_spmm_rows_kernel.h)
+    int vec_out;           // a lane's 4 results can leave as one 16-byte store
 };
 
 struct SpmmLaunch {
@@ -67,6 +71,64 @@ int spmm_launch_f16(int ch, int lpr, int u, int q, const SpmmArgs& a, const Spmm
 
 #ifdef __HIPCC__
 
+// The tile of X (slab_rows rows of f4_per_row float4, starting at row j0*B and column n0)
+// goes to LDS at Xs, row-major.  Direct-to-LDS loads are not tracked by the compiler: the
+// caller waits for them (wait_vm_and_lds) before its barrier.
+__device__ __forceinline__ void spmm_stage_tile(const SpmmArgs& a, float* Xs, int j0, int n0, int ntw,
+                                                int slab_rows, int f4_per_row, int f4_shift, int tid,
+                                                int nthr) {
+    const float* Xg = a.X + (size_t)j0 * a.B * a.ldx + n0;
+    const int total_f4 = slab_rows * f4_per_row;
+    if (a.dma) {
+        // A lane's pieces are nthr float4 apart: the same column group every time and a
+        // constant number of rows further on (f4_per_row is a power of two <= 64), so the
+        // source address advances by a constant.
+        const int wave = tid >> 6, n_waves = nthr >> 6;
+        const int c4 = tid & (f4_per_row - 1);
+        // columns past the tile's live width are never read back as results
+        const float* src = Xg + (size_t)(tid >> f4_shift) * a.ldx + min(c4 * 4, max(ntw - 4, 0));
+        const size_t src_step = (size_t)(nthr >> f4_shift) * a.ldx;
+        int i = tid;
+        for (int p = wave; p * 64 < total_f4; p += n_waves, i += nthr, src += src_step) {
+            if (i < total_f4)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)src,
+                    (__attribute__((address_space(3))) void*)(Xs + p * 256), 16, 0, 0);
+        }
+    } else {
+        for (int i = tid; i < total_f4; i += nthr) {
+            const int r = i >> f4_shift, c4 = i & (f4_per_row - 1);
+            const float* src = Xg + (size_t)r * a.ldx + c4 * 4;
+            float4 t;
+            t.x = c4 * 4 + 0 < ntw ? src[0] : 0.f;
+            t.y = c4 * 4 + 1 < ntw ? src[1] : 0.f;
+            t.z = c4 * 4 + 2 < ntw ? src[2] : 0.f;
+            t.w = c4 * 4 + 3 < ntw ? src[3] : 0.f;
+            reinterpret_cast<float4*>(Xs)[i] = t;
+        }
+    }
+}
+
+// workgroup number -> (column tile z, slab s, row group g); consecutive numbers share an
+// XCD.  Multiply-high by host-made reciprocals: run-time divisions cost ~30 instructions each.
+__device__ __forceinline__ bool spmm_which_tile(const SpmmArgs& a, int& z, int& s, int& g) {
+    const int b = blockIdx.x;
+    const int wg = (b % kXcds) * a.wgs_per_xcd + b / kXcds;
+    if (wg >= a.total_wgs) return false;
+    const uint32_t rgs = (uint32_t)(a.row_groups * a.n_slabs);
+    z = (int)div_magic_any((uint32_t)wg, rgs, a.magic_rgs);
+    const uint32_t in_tile = (uint32_t)wg - (uint32_t)z * rgs;
+    s = (int)div_magic_any(in_tile, (uint32_t)a.row_groups, a.magic_rg);
+    g = (int)(in_tile - (uint32_t)s * (uint32_t)a.row_groups);
+    return true;
+}
+
+// A lane's four column sums, as one 128-bit register tuple: kept as four separate
+// registers the compiler has been seen to move them through a tuple whose other half
+// was a register a load was about to fill, which made the consuming code wait for that
+// load.  (Q, the number of such groups per lane, is 1 in every instantiation.)
+typedef float SpmmAcc __attribute__((ext_vector_type(4)));
+
 // One chunk slot: CH entries, each one 16-byte gather per Q and 4*Q multiply-adds.
 // MASKED: lanes past the end of the run hold a re-read of the run's last chunk; they
 // gather that chunk's own rows of X (operands this matrix row uses anyway) and
@@ -74,7 +136,7 @@ int spmm_launch_f16(int ch, int lpr, int u, int q, const SpmmArgs& a, const Spmm
 template <typename VT, int CH, int Q, bool MASKED, typename VRaw, typename IRaw>
 __device__ __forceinline__ void spmm_slot(const char* xcol, const uint32_t* tab, uint32_t pitch,
                                           const VRaw& v, const IRaw& o, int c, int cps,
-                                          float (&acc)[4 * Q]) {
+                                          SpmmAcc& acc) {
     const bool ok = c < cps;
     const uint32_t* t = tab + min(c, cps - 1) * CH;
     uint32_t base[CH];
@@ -110,7 +172,7 @@ __device__ __forceinline__ void spmm_slot(const char* xcol, const uint32_t* tab,
 template <typename VT, int CH, int LPR, int U, int Q, int NL, typename VRaw, typename IRaw>
 __device__ __forceinline__ void spmm_slots(const char* xcol, const uint32_t* tab, uint32_t pitch,
                                            const VRaw (&v)[U], const IRaw (&o)[U], int c0, bool ragged,
-                                           int cps, float (&acc)[4 * Q]) {
+                                           int cps, SpmmAcc& acc) {
 #pragma unroll
     for (int u = 0; u < NL - 1; ++u)
         spmm_slot<VT, CH, Q, false>(xcol, tab, pitch, v[u], o[u], c0 + u * LPR, cps, acc);
@@ -128,7 +190,7 @@ __device__ __forceinline__ void spmm_slots(const char* xcol, const uint32_t* tab
 template <typename VT, int CH, int LPR, int U, int Q, typename VRaw, typename IRaw>
 __device__ __forceinline__ void spmm_consume(const char* xcol, const uint32_t* tab, uint32_t pitch,
                                              const VRaw (&v)[U], const IRaw (&o)[U], int c0,
-                                             int round_base, int cps, float (&acc)[4 * Q]) {
+                                             int round_base, int cps, SpmmAcc& acc) {
     static_assert(U == 2 || U == 4, "cases below");
     const int left = cps - round_base;                    // chunks of the run from this round on
     const int live = left >= U * LPR ? U : (left + LPR - 1) / LPR;
@@ -143,20 +205,13 @@ __device__ __forceinline__ void spmm_consume(const char* xcol, const uint32_t* t
 
 template <typename VT, int CH, int LPR, int U, int Q>
 __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
+    static_assert(Q == 1, "one group of four columns per lane");
     extern __shared__ __align__(16) float Xs[];
     using VRaw = typename RawBytes<CH * sizeof(VT)>::type;
     using IRaw = typename RawBytes<CH>::type;
 
-    // workgroup number -> (tile, slab, row group); consecutive numbers share an XCD
-    const int b = blockIdx.x;
-    const int wg = (b % kXcds) * a.wgs_per_xcd + b / kXcds;
-    if (wg >= a.total_wgs) return;
-    // multiply-high by host-made reciprocals: run-time divisions cost ~30 instructions each
-    const uint32_t rgs = (uint32_t)(a.row_groups * a.n_slabs);
-    const int z = (int)div_magic_any((uint32_t)wg, rgs, a.magic_rgs);
-    const uint32_t in_tile = (uint32_t)wg - (uint32_t)z * rgs;
-    const int s = (int)div_magic_any(in_tile, (uint32_t)a.row_groups, a.magic_rg);
-    const int g = (int)(in_tile - (uint32_t)s * (uint32_t)a.row_groups);
+    int z, s, g;
+    if (!spmm_which_tile(a, z, s, g)) return;
 
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int j0 = s * a.sb;
@@ -183,59 +238,41 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
     const int r_end = min(a.M, r_begin + a.rows_per_wg);
 
     // (1) the tile of X -> LDS
-    const float* Xg = a.X + (size_t)j0 * a.B * a.ldx + n0;
-    const int total_f4 = slab_rows * f4_per_row;
-    if (a.dma) {
-        // A lane's pieces are nthr float4 apart: the same column group every time and a
-        // constant number of rows further on (f4_per_row is a power of two <= 64), so the
-        // source address advances by a constant.
-        const int wave = tid >> 6, n_waves = nthr >> 6;
-        const int c4 = tid & (f4_per_row - 1);
-        // columns past the tile's live width are never read back as results
-        const float* src = Xg + (size_t)(tid >> f4_shift) * a.ldx + min(c4 * 4, max(ntw - 4, 0));
-        const size_t src_step = (size_t)(nthr >> f4_shift) * a.ldx;
-        int i = tid;
-        for (int p = wave; p * 64 < total_f4; p += n_waves, i += nthr, src += src_step) {
-            if (i < total_f4)
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)src,
-                    (__attribute__((address_space(3))) void*)(Xs + p * 256), 16, 0, 0);
-        }
-    } else {
-        for (int i = tid; i < total_f4; i += nthr) {
-            const int r = i >> f4_shift, c4 = i & (f4_per_row - 1);
-            const float* src = Xg + (size_t)r * a.ldx + c4 * 4;
-            float4 t;
-            t.x = c4 * 4 + 0 < ntw ? src[0] : 0.f;
-            t.y = c4 * 4 + 1 < ntw ? src[1] : 0.f;
-            t.z = c4 * 4 + 2 < ntw ? src[2] : 0.f;
-            t.w = c4 * 4 + 3 < ntw ? src[3] : 0.f;
-            reinterpret_cast<float4*>(Xs)[i] = t;
-        }
-    }
+    spmm_stage_tile(a, Xs, j0, n0, ntw, slab_rows, f4_per_row, f4_shift, tid, nthr);
     pin_order();
 
-    // (2) first pass of the weight stream: exactly 2*U loads between the pins
+    // (2) the weight stream in rounds of U*LPR chunks of a row: a row's run takes `rounds`
+    // of them, a lane walks n_passes rows.  First round: exactly 2*U loads between the pins.
     const VT* vbase = static_cast<const VT*>(a.vals);
     VRaw vA[U], vB[U];
     IRaw oA[U], oB[U];
-    auto row_ptrs = [&](int r, const VRaw*& vrow, const IRaw*& irow) {
-        const int rc = min(r, a.M - 1);
+    const int rounds = (cps + U * LPR - 1) / (U * LPR);
+    const int total = a.n_passes * rounds;
+    const int r_first = r_begin + slot;
+    int ld_pass = 0, ld_round = 0;               // wavefront-uniform
+    const VRaw* ld_v;
+    const IRaw* ld_i;
+    auto set_row = [&](int pass) {
+        // rows past the workgroup's range re-read its last row (never stored)
+        const int rc = min(r_first + pass * rows_per_pass, r_end - 1);
         const size_t e0 = ((size_t)rc * a.nb + j0) * a.k;
-        vrow = reinterpret_cast<const VRaw*>(vbase + e0);
-        irow = reinterpret_cast<const IRaw*>(a.idx + e0);
+        ld_v = reinterpret_cast<const VRaw*>(vbase + e0);
+        ld_i = reinterpret_cast<const IRaw*>(a.idx + e0);
     };
-    int r = r_begin + slot;
-    {
-        const VRaw* vrow; const IRaw* irow;
-        row_ptrs(r, vrow, irow);
+    auto issue = [&]() {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int c = min(l + u * LPR, cps - 1);
-            vA[u] = vrow[c];
-            oA[u] = irow[c];
+            const int c = min(ld_round * (U * LPR) + l + u * LPR, cps - 1);
+            vB[u] = ld_v[c];
+            oB[u] = ld_i[c];
         }
-    }
+        if (++ld_round == rounds) {
+            ld_round = 0;
+            set_row(++ld_pass);
+        }
+    };
+    set_row(0);
+    issue();
     pin_order();
 
     // (2b) position table: byte offset of the LDS rows of the bank an entry is in
@@ -251,66 +288,42 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
     const char* xcol = reinterpret_cast<const char*>(Xs) + cg * (Q * 16);
     float* outp = a.out + (size_t)s * a.slab_stride;
 
-    auto finish_row = [&](int row, const VRaw (&v)[U], const IRaw (&o)[U]) {
-        float acc[4 * Q];
+    // (4) The loads of a round always land in set B; the round is consumed from set A, a
+    // copy made once they have arrived, while the loads of the next round (of the same row
+    // or of the lane's next row) are in flight.  Set A is never the target of a load, so
+    // nothing in the consuming code waits for memory.  (With the loop unrolled twice over
+    // two load targets the compiler loses track of which loads are outstanding at the
+    // loop head and makes the consuming code wait for the loads that were just issued.)
+    // Round and pass counts are the same for every lane.
+    SpmmAcc acc = {0.f, 0.f, 0.f, 0.f};
+    int cs_pass = 0, cs_round = 0;               // wavefront-uniform
+    for (int t = 0; t < total; ++t) {
 #pragma unroll
-        for (int n = 0; n < 4 * Q; ++n) acc[n] = 0.f;
-        spmm_consume<VT, CH, LPR, U, Q>(xcol, tab, pitch, v, o, l, 0, cps, acc);
-        if (cps > U * LPR) {   // long runs: further rounds, loaded and consumed in place
-            const VRaw* vrow; const IRaw* irow;
-            row_ptrs(row, vrow, irow);
-            for (int c0 = l + U * LPR; c0 - l < cps; c0 += U * LPR) {
-                VRaw vt[U];
-                IRaw ot[U];
+        for (int u = 0; u < U; ++u) { vA[u] = vB[u]; oA[u] = oB[u]; }
+        pin_order();
+        if (t + 1 < total) issue();
+        pin_order();
+        const int round_base = cs_round * (U * LPR);
+        spmm_consume<VT, CH, LPR, U, Q>(xcol, tab, pitch, vA, oA, round_base + l, round_base, cps, acc);
+        if (++cs_round == rounds) {
+            // the LPR lanes of a (row, column group) are nl lanes apart
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int c = min(c0 + u * LPR, cps - 1);
-                    vt[u] = vrow[c];
-                    ot[u] = irow[c];
-                }
-                spmm_consume<VT, CH, LPR, U, Q>(xcol, tab, pitch, vt, ot, c0, c0 - l, cps, acc);
+            for (int step = 1; step < LPR; step <<= 1) {
+#pragma unroll
+                for (int n = 0; n < 4; ++n) acc[n] += __shfl_xor(acc[n], step * nl, kWave);
             }
-        }
-        // the LPR lanes of a (row, column group) are nl lanes apart
+            const int row = r_first + cs_pass * rows_per_pass;
+            if (l == 0 && row < r_end) {
+                float* dst = outp + (size_t)row * a.ld_out + n0 + cg * 4;
 #pragma unroll
-        for (int step = 1; step < LPR; step <<= 1) {
-#pragma unroll
-            for (int n = 0; n < 4 * Q; ++n) acc[n] += __shfl_xor(acc[n], step * nl, kWave);
-        }
-        if (l == 0 && row < r_end) {
-            float* dst = outp + (size_t)row * a.ld_out + n0 + cg * (4 * Q);
-#pragma unroll
-            for (int n = 0; n < 4 * Q; ++n)
-                if (cg * (4 * Q) + n < ntw) dst[n] = acc[n];
-        }
-    };
-
-    // (4) row passes, two register sets: the next pass is in flight while this one
-    // is consumed.  All lanes of a (row, column group) share `r`, so they leave together.
-    for (; r < r_end; r += 2 * rows_per_pass) {
-        if (r + rows_per_pass < r_end) {
-            const VRaw* vrow; const IRaw* irow;
-            row_ptrs(r + rows_per_pass, vrow, irow);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int c = min(l + u * LPR, cps - 1);
-                vB[u] = vrow[c];
-                oB[u] = irow[c];
+                for (int n = 0; n < 4; ++n)
+                    if (cg * 4 + n < ntw) dst[n] = acc[n];
             }
+            acc = SpmmAcc{0.f, 0.f, 0.f, 0.f};
+            cs_round = 0;
+            ++cs_pass;
         }
-        finish_row(r, vA, oA);
-        if (r + rows_per_pass >= r_end) break;
-        if (r + 2 * rows_per_pass < r_end) {
-            const VRaw* vrow; const IRaw* irow;
-            row_ptrs(r + 2 * rows_per_pass, vrow, irow);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int c = min(l + u * LPR, cps - 1);
-                vA[u] = vrow[c];
-                oA[u] = irow[c];
-            }
-        }
-        finish_row(r + rows_per_pass, vB, oB);
+        pin_order();
     }
 }
 

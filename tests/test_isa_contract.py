@@ -19,7 +19,8 @@ import pytest
 
 from paper_1811_00206_amd import build as bs_build
 
-SOURCES = ["bs_spmv_f32.hip", "bs_spmv_f16.hip", "bs_spmm_f32.hip", "bs_spmm_f16.hip"]
+SOURCES = ["bs_spmv_f32.hip", "bs_spmv_f16.hip", "bs_spmm_f32.hip", "bs_spmm_f16.hip",
+           "bs_spmm_rows.hip"]
 
 
 def _assembly(src):
@@ -35,11 +36,12 @@ def _assembly(src):
 
 def _kernels(text):
     """name -> list of instruction lines (plus the "; bs_pin" markers that
-    pin_order() leaves), for every spmv_kernel / spmm_kernel instantiation."""
+    pin_order() leaves), for every spmv_kernel / spmm_kernel / spmm_rows_kernel
+    instantiation."""
     out = {}
     cur = None
     for line in text.splitlines():
-        m = re.match(r"^(_ZN2bs11sp(?:mv|mm)_kernel\w+):", line)
+        m = re.match(r"^(_ZN2bs(?:11sp(?:mv|mm)_kernel|16spmm_rows_kernel)\w+):", line)
         if m:
             cur = m.group(1)
             out[cur] = []
@@ -75,6 +77,8 @@ def test_every_instantiation_is_present(kernels):
     # and 2 depths for SpMM
     assert sum("spmv_kernel" in n for n in kernels) == (3 + 4) * 7 * 4 + (3 + 4) * 4 * 2
     assert sum("spmm_kernel" in n for n in kernels) == (3 + 4) * 5 * 2
+    # one lane per (row, column group): chunk widths only
+    assert sum("spmm_rows_kernel" in n for n in kernels) == 3 + 4
 
 
 def test_wait_before_barrier_covers_the_copy_of_x(kernels):
