@@ -131,22 +131,37 @@ SpmmPlan make_plan(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N) 
 }
 
 // Y[r][n] = sum over slabs, in slab order.  magic_n = magic_u32(N): rows from element
-// numbers without a 64-bit division (M*N < 2^31 is checked by the caller).
+// numbers without a 64-bit division (M*N < 2^32 is checked by the caller).
+// V = floats per lane and step: 4 when N, ldy and Y's address allow 16-byte accesses.
+template <int V>
 __global__ __launch_bounds__(256) void spmm_reduce_kernel(const float* __restrict__ P,
                                                           float* __restrict__ Y, int64_t M,
                                                           int64_t N, int64_t ldy, int n_slabs,
                                                           uint32_t magic_n) {
     const int64_t total = M * N;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        float acc = P[i];
-        for (int s = 1; s < n_slabs; ++s) acc += P[(int64_t)s * total + i];
-        if (ldy == N) {
-            Y[i] = acc;
+    const int64_t steps = total / V;                       // V divides N
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < steps;
+         j += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t i = j * V;
+        float acc[V];
+        if constexpr (V == 4) {
+            const float4 t = *reinterpret_cast<const float4*>(P + i);
+            acc[0] = t.x; acc[1] = t.y; acc[2] = t.z; acc[3] = t.w;
+            for (int s = 1; s < n_slabs; ++s) {
+                const float4 u = *reinterpret_cast<const float4*>(P + (int64_t)s * total + i);
+                acc[0] += u.x; acc[1] += u.y; acc[2] += u.z; acc[3] += u.w;
+            }
         } else {
-            const uint32_t r = div_magic_any((uint32_t)i, (uint32_t)N, magic_n);
-            Y[(int64_t)r * ldy + ((uint32_t)i - r * (uint32_t)N)] = acc;
+            acc[0] = P[i];
+            for (int s = 1; s < n_slabs; ++s) acc[0] += P[(int64_t)s * total + i];
         }
+        int64_t o = i;
+        if (ldy != N) {
+            const uint32_t r = div_magic_any((uint32_t)i, (uint32_t)N, magic_n);
+            o = (int64_t)r * ldy + ((uint32_t)i - r * (uint32_t)N);
+        }
+        if constexpr (V == 4) *reinterpret_cast<float4*>(Y + o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        else Y[o] = acc[0];
     }
 }
 
@@ -198,10 +213,14 @@ int launch_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int6
                                     : spmm_launch_f32(p.ch, p.lpr, p.u, p.q, a, l);
     if (st_code != BS_OK) return st_code;
     if (p.n_slabs > 1) {
-        const int64_t tot = M * N;
-        int64_t grid = (tot + 255) / 256;
+        // 16 bytes per lane where rows of Y and of the workspace allow it (the workspace is
+        // 16-byte aligned, its rows are N floats)
+        const bool vec = N % 4 == 0 && ldy % 4 == 0 && (uintptr_t)Y % 16 == 0;
+        const int64_t steps = M * N / (vec ? 4 : 1);
+        int64_t grid = (steps + 255) / 256;
         if (grid > 256 * 16) grid = 256 * 16;
-        hipLaunchKernelGGL(spmm_reduce_kernel, dim3((unsigned)grid), dim3(256), 0, st,
+        auto kern = vec ? spmm_reduce_kernel<4> : spmm_reduce_kernel<1>;
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), 0, st,
                            static_cast<const float*>(workspace), Y, M, N, ldy, p.n_slabs,
                            magic_u32((uint32_t)N));
         return hip_status(hipGetLastError());

@@ -208,7 +208,7 @@ def check_spmm(W, bank, k, X, tol):
 
 
 @pytest.mark.parametrize("M,K,bank,k", SMALL_SHAPES)
-@pytest.mark.parametrize("N", [1, 2, 3, 4, 7, 8, 33, 130])
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 7, 8, 16, 20, 33, 64, 130])
 def test_spmm_small(M, K, bank, k, N):
     say("spmm small", M, K, bank, k, N)
     W = workloads.draw_weights(M, K, 0.05, "f32", 35)
