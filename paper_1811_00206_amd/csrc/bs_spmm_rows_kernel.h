@@ -204,8 +204,16 @@ __global__ __launch_bounds__(1024) void spmm_rows_kernel(SpmmArgs a) {
             const int c = cs_round * RC + u * 4;
             const uint32_t* t = tab + c * CH;
             if (c + 3 < cps) {
-                spmm_rows_chunks<VT, CH, 0, 2>(xcol, t, pitch_shift, v[u], o[u], acc);
-                spmm_rows_chunks<VT, CH, 2, 2>(xcol, t + 2 * CH, pitch_shift, v[u], o[u], acc);
+                // 8 gathers in flight: two chunks of 4 entries, or one of 8 (more would spill)
+                if constexpr (CH <= 4) {
+                    spmm_rows_chunks<VT, CH, 0, 2>(xcol, t, pitch_shift, v[u], o[u], acc);
+                    spmm_rows_chunks<VT, CH, 2, 2>(xcol, t + 2 * CH, pitch_shift, v[u], o[u], acc);
+                } else {
+                    spmm_rows_chunks<VT, CH, 0, 1>(xcol, t, pitch_shift, v[u], o[u], acc);
+                    spmm_rows_chunks<VT, CH, 1, 1>(xcol, t + CH, pitch_shift, v[u], o[u], acc);
+                    spmm_rows_chunks<VT, CH, 2, 1>(xcol, t + 2 * CH, pitch_shift, v[u], o[u], acc);
+                    spmm_rows_chunks<VT, CH, 3, 1>(xcol, t + 3 * CH, pitch_shift, v[u], o[u], acc);
+                }
             } else {
                 if (c + 0 < cps) spmm_rows_chunks<VT, CH, 0, 1>(xcol, t, pitch_shift, v[u], o[u], acc);
                 if (c + 1 < cps) spmm_rows_chunks<VT, CH, 1, 1>(xcol, t + CH, pitch_shift, v[u], o[u], acc);

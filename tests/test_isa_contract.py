@@ -62,9 +62,13 @@ def _is_vmem_load(ins):
 
 
 @pytest.fixture(scope="module")
-def kernels():
+def texts():
     with ThreadPoolExecutor(4) as ex:
-        texts = list(ex.map(_assembly, SOURCES))
+        return list(ex.map(_assembly, SOURCES))
+
+
+@pytest.fixture(scope="module")
+def kernels(texts):
     ks = {}
     for t in texts:
         ks.update(_kernels(t))
@@ -104,3 +108,16 @@ def test_wait_before_barrier_covers_the_copy_of_x(kernels):
             f"{name}: a load between the second pin and the barrier would break the count")
         # no LDS read before the barrier at all
         assert not any(s.startswith("ds_read") for s in ins[:barrier]), name
+
+
+def test_no_kernel_spills_registers(texts):
+    """Every SpMV / SpMM instantiation fits its register budget: a spill would put scratch
+    memory traffic into the inner loops (seen once with 16 gathers in flight)."""
+    n = 0
+    for t in texts:
+        for m in re.finditer(r"\.(vgpr|sgpr)_spill_count:\s+(\d+)", t):
+            n += 1
+            assert int(m.group(2)) == 0, f"{m.group(1)} spills: {m.group(2)}"
+        for m in re.finditer(r"\.private_segment_fixed_size:\s+(\d+)", t):
+            assert int(m.group(1)) == 0, "a kernel uses scratch memory"
+    assert n > 0
