@@ -130,6 +130,23 @@ int bs_spmv_ex(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64
  * bs_spmm_workspace_bytes(...) bytes (may be NULL when that is 0).
  */
 size_t bs_spmm_workspace_bytes(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N);
+
+/*
+ * The launch bs_spmm would make for this shape, for tests and tuning (host only, no GPU
+ * call; the tiling itself is ours, the paper gives none for a batch).  Writes up to n_out
+ * of these 16 values to out (HOST):
+ *   [0] kernel: 0 chunk walk (LPR lanes per row and column group), 1 one lane per row and
+ *       column group          [1] entries per 16-byte chunk
+ *   [2] column groups of 4 per tile (nl)   [3] columns per tile   [4] column tiles
+ *   [5] banks per K slab       [6] K slabs  [7] lanes per (row, column group)
+ *   [8] chunk slots per lane   [9] threads per workgroup   [10] rows per workgroup
+ *   [11] row groups            [12] row passes of a workgroup
+ *   [13] LDS bytes per workgroup            [14] workgroups launched
+ *   [15] float index of the position table in LDS
+ * Returns BS_OK, or the status bs_spmm would return for an unsupported shape.
+ */
+int bs_spmm_plan(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N,
+                 int64_t* out, int n_out);
 int bs_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K,
             int bank, int k, const float* X, int64_t N, int64_t ldx,
             float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);

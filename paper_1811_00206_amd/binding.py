@@ -20,7 +20,7 @@ BS_F32, BS_F16 = 0, 1
 
 EXPORTS = (
     "bs_nnz", "bs_vals_bytes", "bs_idx_bytes", "bs_status_str", "bs_prune_pack", "bs_spmv",
-    "bs_spmv_ex", "bs_spmm_workspace_bytes", "bs_spmm", "bs_dense_gemv", "bs_dense_gemm",
+    "bs_spmv_ex", "bs_spmm_workspace_bytes", "bs_spmm_plan", "bs_spmm", "bs_dense_gemv", "bs_dense_gemm",
     "bs_lstm_step", "bs_lstm_sequence", "bs_reprune", "bs_probe_empty", "bs_probe_stream_read",
 )
 
@@ -62,6 +62,8 @@ def load_library():
     lib.bs_spmv_ex.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, vp, i32, i32, vp, vp, vp]
     lib.bs_spmm_workspace_bytes.argtypes = [i32, i64, i64, i32, i32, i64]
     lib.bs_spmm_workspace_bytes.restype = sz
+    lib.bs_spmm_plan.argtypes = [i32, i64, i64, i32, i32, i64, ctypes.POINTER(ctypes.c_int64), i32]
+    lib.bs_spmm_plan.restype = i32
     lib.bs_spmm.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, i64, vp, i64, vp, sz, vp]
     lib.bs_dense_gemv.argtypes = [vp, i32, i64, i64, vp, vp, vp]
     lib.bs_dense_gemm.argtypes = [vp, i32, i64, i64, vp, i64, i64, vp, i64, vp]
@@ -146,6 +148,17 @@ def bs_status_str(status: int) -> str:
 
 def bs_spmm_workspace_bytes(dtype: int, M: int, K: int, bank: int, k: int, N: int) -> int:
     return load_library().bs_spmm_workspace_bytes(dtype, M, K, bank, k, N)
+
+
+SPMM_PLAN_FIELDS = ("rows_kernel", "ch", "nl", "nt", "n_tiles", "sb", "n_slabs", "lpr", "u", "threads",
+                    "rows_per_wg", "row_groups", "n_passes", "lds_bytes", "workgroups", "table_off")
+
+
+def bs_spmm_plan(dtype: int, M: int, K: int, bank: int, k: int, N: int) -> dict:
+    """The launch bs_spmm would make (host only).  Raises on an unsupported shape."""
+    out = (ctypes.c_int64 * len(SPMM_PLAN_FIELDS))()
+    _check(load_library().bs_spmm_plan(dtype, M, K, bank, k, N, out, len(SPMM_PLAN_FIELDS)), "bs_spmm_plan")
+    return dict(zip(SPMM_PLAN_FIELDS, (int(v) for v in out)))
 
 
 # --------------------------------------------------------------- GPU calls

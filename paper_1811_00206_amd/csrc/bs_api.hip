@@ -145,6 +145,14 @@ size_t bs_spmm_workspace_bytes(int dtype, int64_t M, int64_t K, int bank, int k,
     return bs::spmm_workspace_bytes(dtype, M, K, bank, k, N);
 }
 
+int bs_spmm_plan(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N, int64_t* out,
+                 int n_out) {
+    if (!out) return BS_ERR_NULL;
+    if (!shape_ok(M, K, bank, k) || N < 1 || n_out < 0) return BS_ERR_SHAPE;
+    if (!dtype_ok(dtype) || !size_ok(M, K, bank)) return BS_ERR_UNSUPPORTED;
+    return bs::spmm_plan_describe(dtype, M, K, bank, k, N, out, n_out);
+}
+
 int bs_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
             int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
             void* workspace, size_t workspace_bytes, void* stream) {

@@ -28,6 +28,8 @@ int launch_lstm_step(const void* vals, const uint8_t* idx, int dtype, int64_t H,
                      int k, const float* x, const float* h_in, const float* bias,
                      const float* c_in, float* c_out, float* h_out, hipStream_t st);
 size_t spmm_workspace_bytes(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N);
+int spmm_plan_describe(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N, int64_t* out,
+                       int n_out);
 int launch_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
                 int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
                 void* workspace, size_t workspace_bytes, hipStream_t st);

@@ -172,6 +172,23 @@ size_t spmm_workspace_bytes(int dtype, int64_t M, int64_t K, int bank, int k, in
     return p.ok ? p.ws_bytes : 0;
 }
 
+int spmm_plan_describe(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N, int64_t* out,
+                       int n_out) {
+    if (M > INT32_MAX / 4 || N > INT32_MAX / 4) return BS_ERR_UNSUPPORTED;
+    const SpmmPlan p = make_plan(dtype, M, K, bank, k, N);
+    if (!p.ok || p.lds_bytes > (size_t)kMaxLdsBytes) return BS_ERR_UNSUPPORTED;
+    const int64_t total = (int64_t)p.n_tiles * p.n_slabs * p.row_groups;
+    if (total > INT32_MAX / 2) return BS_ERR_UNSUPPORTED;
+    if (p.ws_bytes && M * N > (int64_t)UINT32_MAX) return BS_ERR_UNSUPPORTED;
+    const int rows_per_pass = p.threads / (p.nl * p.lpr);
+    const int64_t v[16] = {p.rows ? 1 : 0, p.ch, p.nl, p.nt, p.n_tiles, p.sb, p.n_slabs, p.lpr, p.u,
+                           p.threads, p.rows_per_wg, p.row_groups,
+                           (p.rows_per_wg + rows_per_pass - 1) / rows_per_pass,
+                           (int64_t)p.lds_bytes, (total + kXcds - 1) / kXcds * kXcds, p.table_off};
+    for (int i = 0; i < n_out && i < 16; ++i) out[i] = v[i];
+    return BS_OK;
+}
+
 int launch_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
                 int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
                 void* workspace, size_t workspace_bytes, hipStream_t st) {

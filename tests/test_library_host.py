@@ -77,3 +77,82 @@ def test_bad_arguments_are_refused_before_launch():
     assert lib.bs_spmv_ex(p, p, 0, 4, 8, 4, 2, p, p, 16, 3, null, null, null) == 3   # 48 lanes per workgroup
     assert lib.bs_dense_gemv(p, 0, 0, 8, p, p, null) == 2
     assert lib.bs_dense_gemm(p, 0, 4, 8, p, 4, 2, p, 4, null) == 2
+
+
+def _plan_invariants(b, dtype, M, K, bank, k, N):
+    """What the SpMM kernels assume about their launch, checked on the host for one shape."""
+    vsize = 2 if dtype == b.BS_F16 else 4
+    p = b.bs_spmm_plan(dtype, M, K, bank, k, N)
+    nb = K // bank
+    where = f"{(dtype, M, K, bank, k, N)} -> {p}"
+    # tile geometry
+    assert p["nl"] in (1, 2, 4, 8, 16) and p["nt"] == 4 * p["nl"], where
+    assert p["n_tiles"] * p["nt"] >= N > (p["n_tiles"] - 1) * p["nt"], where
+    assert 1 <= p["sb"] <= nb and p["n_slabs"] == -(-nb // p["sb"]), where
+    # chunks: whole 16-byte (or narrower) chunks in every slab's run, including the last slab's
+    assert p["ch"] in (1, 2, 4, 8) and p["ch"] * vsize <= 16, where
+    assert (nb * k) % p["ch"] == 0, where
+    last = nb - (p["n_slabs"] - 1) * p["sb"]
+    for banks in {p["sb"], last}:
+        assert (banks * k) % p["ch"] == 0, where
+    if p["n_slabs"] > 1:
+        assert (p["sb"] * k * vsize) % (p["ch"] * vsize) == 0, where   # slab starts stay chunk-aligned
+    # LDS: tile, then the position table
+    tile = p["sb"] * bank * p["nl"] * 16
+    assert p["table_off"] * 4 == tile, where
+    assert p["lds_bytes"] == tile + p["sb"] * k * 4 <= 160 * 1024, where
+    # lanes
+    assert p["threads"] % 64 == 0 and 64 <= p["threads"] <= 1024, where
+    if p["rows_kernel"]:
+        assert p["nl"] >= 4 and p["lpr"] == 1 and p["u"] == 4, where
+    else:
+        assert p["lpr"] in (4, 8, 16, 32, 64) and p["u"] in (2, 4) and p["nl"] * p["lpr"] <= 64, where
+    rows_per_pass = p["threads"] // (p["nl"] * p["lpr"])
+    assert rows_per_pass >= 1, where
+    # rows: every row in exactly one group, every row of a group in one pass
+    assert p["row_groups"] * p["rows_per_wg"] >= M > (p["row_groups"] - 1) * p["rows_per_wg"], where
+    assert p["n_passes"] * rows_per_pass >= p["rows_per_wg"] > (p["n_passes"] - 1) * rows_per_pass, where
+    # grid: a multiple of the 8 XCDs that covers every (tile, slab, row group)
+    total = p["n_tiles"] * p["n_slabs"] * p["row_groups"]
+    assert p["workgroups"] % 8 == 0 and total <= p["workgroups"] < total + 8, where
+    # workspace: partial sums of every slab, or none
+    ws = b.bs_spmm_workspace_bytes(dtype, M, K, bank, k, N)
+    assert ws == (p["n_slabs"] * M * N * 4 if p["n_slabs"] > 1 else 0), where
+    return p
+
+
+def test_spmm_plan_invariants_on_the_paper_shapes():
+    from paper_1811_00206_amd import binding as b
+    seen = set()
+    for dtype, M, K, bank, k, Ns in [
+            (b.BS_F32, 256, 256, 64, 16, (1, 8)),
+            (b.BS_F32, 6000, 3000, 100, 10, (1, 8, 32, 128)),
+            (b.BS_F32, 4096, 4096, 64, 32, (1, 8)),
+            (b.BS_F16, 4096, 25088, 64, 6, (1, 16)),
+            (b.BS_F32, 16384, 8192, 256, 128, (1, 8)),
+            (b.BS_F32, 16384, 8192, 256, 8, (8,)),
+            (b.BS_F32, 512, 4608, 64, 16, (196, 784)),
+            (b.BS_F32, 128, 576, 64, 16, (12544,))]:
+        for N in Ns:
+            seen.add(_plan_invariants(b, dtype, M, K, bank, k, N)["rows_kernel"])
+    assert seen == {0, 1}       # both kernels are in use on these shapes
+
+
+def test_spmm_plan_invariants_random_shapes():
+    import random
+    from paper_1811_00206_amd import binding as b
+    rng = random.Random(1811_00206)
+    done = 0
+    for _ in range(4000):
+        bank = rng.choice([1, 2, 3, 4, 5, 8, 16, 25, 32, 50, 64, 100, 128, 200, 255, 256])
+        nb = rng.choice([1, 2, 3, 7, 30, 32, 64, 100, 392, 1000])
+        k = rng.randint(1, bank)
+        M = rng.choice([1, 2, 63, 64, 65, 500, 1000, 4096, 6000, 16384, 100000])
+        N = rng.choice([1, 2, 3, 4, 5, 8, 12, 16, 17, 31, 32, 33, 64, 100, 128, 196, 784, 1000, 12544])
+        dtype = rng.choice([b.BS_F32, b.BS_F16])
+        try:
+            _plan_invariants(b, dtype, M, bank * nb, bank, k, N)
+            done += 1
+        except b.BsError as e:                       # a documented refusal, never a bad plan
+            assert "unsupported" in str(e), (dtype, M, bank * nb, bank, k, N, str(e))
+    assert done > 3000
