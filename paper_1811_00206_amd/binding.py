@@ -163,8 +163,9 @@ def bs_spmm_plan(dtype: int, M: int, K: int, bank: int, k: int, N: int) -> dict:
 
 # --------------------------------------------------------------- GPU calls
 
-def bs_prune_pack(W: torch.Tensor, bank: int, k: int):
-    """W [M, K] on the GPU (fp32/fp16) -> (vals [M, K/bank, k], idx uint8 same shape)."""
+def bs_prune_pack(W: torch.Tensor, bank: int, k: int, out=None):
+    """W [M, K] on the GPU (fp32/fp16) -> (vals [M, K/bank, k], idx uint8 same shape);
+    `out` = (vals, idx) to write into existing tensors."""
     _dev(W, "W")
     code = _dtype_code(W, "W")
     if W.dim() != 2:
@@ -173,8 +174,15 @@ def bs_prune_pack(W: torch.Tensor, bank: int, k: int):
     if bank < 1 or K % bank or k < 1 or k > bank:
         raise BsError(2, "bs_prune_pack")
     nb = K // bank
-    vals = torch.empty((M, nb, k), dtype=W.dtype, device=W.device)
-    idx = torch.empty((M, nb, k), dtype=torch.uint8, device=W.device)
+    if out is None:
+        vals = torch.empty((M, nb, k), dtype=W.dtype, device=W.device)
+        idx = torch.empty((M, nb, k), dtype=torch.uint8, device=W.device)
+    else:
+        vals, idx = out
+        _dev(vals, "vals", W.dtype)
+        _dev(idx, "idx", torch.uint8)
+        if tuple(vals.shape) != (M, nb, k) or tuple(idx.shape) != (M, nb, k):
+            raise ValueError(f"out must be two [{M}, {nb}, {k}] tensors")
     _check(load_library().bs_prune_pack(_ptr(W), code, M, K, bank, k, _ptr(vals), _ptr(idx),
                                         _stream()), "bs_prune_pack")
     return vals, idx

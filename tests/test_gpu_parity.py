@@ -429,3 +429,74 @@ def test_device_side_argument_errors():
     assert e.value.status == 4
     y = bs.bs_spmv(v, i, 4, x)
     assert host(y).tolist() == [0.0] * 4
+
+
+# ------------------------------------------- the launch configuration bench.py times
+
+@pytest.mark.gpu
+def test_graph_replays_match_eager_launches():
+    """bench.py times a captured graph of launches over rotating copies of the packed matrix.
+    The whole path (prune+pack, SpMV, SpMM with its workspace and reduce kernel, a fused LSTM
+    sequence) is captured once and replayed several times, with eager work and
+    synchronisations between the replays; every replay must reproduce the eager results
+    bit for bit (the kernels have a fixed summation order) and the eager results match the
+    oracle."""
+    say("graph replays")
+    wl, W, x = workloads.make("lstm1500", rows=1200)          # 1200 x 3000: H = 300, I = 2700
+    X = workloads.draw_activations(wl.K, 32, wl.seed + 5)
+    Hn, T = 300, 5
+    Xs, h0, c0, bias = workloads.draw_lstm_inputs(Hn, wl.K - Hn, T, wl.seed)
+    v_ref, i_ref = bs_ref.prune_pack(W, wl.bank, wl.k)
+
+    Wd, xd, Xd = dev(W), dev(x), dev(X)
+    Xs_d, h0_d, bias_d = dev(Xs), dev(h0), dev(bias)
+    copies = 3
+    vals = [torch.empty((1200, wl.K // wl.bank, wl.k), dtype=torch.float32, device=DEV) for _ in range(copies)]
+    idx = [torch.empty((1200, wl.K // wl.bank, wl.k), dtype=torch.uint8, device=DEV) for _ in range(copies)]
+    y = [torch.empty(1200, device=DEV) for _ in range(copies)]
+    Y = [torch.empty((1200, 32), device=DEV) for _ in range(copies)]
+    need = bs.bs_spmm_workspace_bytes(bs.BS_F32, 1200, wl.K, wl.bank, wl.k, 32)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=DEV)
+    c = torch.empty(Hn, device=DEV)
+    c0_d = dev(c0)
+    H_all = torch.empty((T, Hn), device=DEV)
+
+    def run_all():
+        for j in range(copies):
+            bs.bs_prune_pack(Wd, wl.bank, wl.k, out=(vals[j], idx[j]))
+            bs.bs_spmv(vals[j], idx[j], wl.bank, xd, out=y[j])
+            bs.bs_spmm(vals[j], idx[j], wl.bank, Xd, out=Y[j], workspace=ws)
+        c.copy_(c0_d)                                         # a copy kernel, no memset node
+        bs.bs_lstm_sequence(vals[0], idx[0], wl.bank, Xs_d, h0_d, bias_d, c, H_all=H_all)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return ([t.cpu().numpy().tobytes() for t in vals + idx + y + Y] +
+                [c.cpu().numpy().tobytes(), H_all.cpu().numpy().tobytes()])
+
+    def scribble():
+        for t in vals + y + Y + [c, H_all]:
+            t.fill_(7.0)
+        for t in idx:
+            t.fill_(7)
+        ws.fill_(255)
+        torch.cuda.synchronize()
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        run_all()                                             # eager, also warms every kernel up
+    eager = snapshot()
+    assert vals[0].cpu().numpy().tobytes() == v_ref.tobytes()
+    assert idx[0].cpu().numpy().tobytes() == i_ref.tobytes()
+    assert bs_ref.rel_l2(host(y[1]), bs_ref.spmv(v_ref, i_ref, wl.bank, x)) <= 1e-5
+    assert bs_ref.rel_l2(host(Y[2]), bs_ref.spmm(v_ref, i_ref, wl.bank, X)) <= 1e-5
+    H_ref, c_ref = bs_ref.lstm_sequence(v_ref, i_ref, wl.bank, Xs, h0, bias, c0)
+    assert bs_ref.rel_l2(host(H_all), H_ref) <= 1e-5 and bs_ref.rel_l2(host(c), c_ref) <= 1e-5
+
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run_all()
+    for replay in range(4):
+        scribble()                                            # eager work between the replays
+        g.replay()
+        assert snapshot() == eager, f"replay {replay} differs from the eager launches"
