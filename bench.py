@@ -361,6 +361,24 @@ def main():
             w_us = kernel_us_of(vals, idx, Xd, Y, wl.bank)
             extras["warm_kernel_us"] = round(w_us, 2)
             extras["warm_GBps_cache_resident"] = round(alg_bytes / w_us / 1e3, 1)
+            # ... and in the protocol of `value` (a graph of launches back to back), which
+            # does not carry the time-stamp method's floor
+            gw = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gw):
+                for _ in range(64):
+                    bs.bs_spmv(vals, idx, wl.bank, Xd, out=Y)
+            gw.replay()
+            torch.cuda.synchronize()
+            s1, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            s1.record()
+            for _ in range(10):
+                gw.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            wg_us = s1.elapsed_time(e1) * 1e3 / 640
+            extras["warm_us_per_launch_graph"] = round(wg_us, 3)
+            extras["warm_GBps_per_launch_graph"] = round(alg_bytes / wg_us / 1e3, 1)
+            del gw
 
         def avg_us(fn, n):
             for _ in range(3):

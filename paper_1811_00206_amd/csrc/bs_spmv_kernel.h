@@ -182,7 +182,19 @@ __device__ __forceinline__ float consume_any(const SpmvArgs& a, const float* xs,
     return consume<VT, CH, LPR, U, 2>(a, xs, v, o, c0, round_base, cpr);
 }
 
-__device__ __forceinline__ float logistic(float v) { return 1.f / (1.f + expf(-v)); }
+// Gate nonlinearities from the hardware's exp2 and reciprocal (each within about 1 ulp):
+// absolute error around 1e-7 on values in (-1, 1), two orders below the 1e-5 parity bar;
+// the library's expf / tanhf are 20-60 instructions each and sat on the critical path of
+// every step.  exp2 overflows to +inf and underflows to 0, which give the right limits.
+__device__ __forceinline__ float exp_fast(float v) {
+    return __builtin_amdgcn_exp2f(v * 1.44269504088896340736f);
+}
+__device__ __forceinline__ float logistic_fast(float v) {
+    return __builtin_amdgcn_rcpf(1.f + exp_fast(-v));
+}
+__device__ __forceinline__ float tanh_fast(float v) {
+    return 1.f - 2.f * __builtin_amdgcn_rcpf(1.f + exp_fast(2.f * v));
+}
 
 // VT: storage type of vals; CH: entries per chunk (CH*sizeof(VT) <= 16, CH divides
 // row_len); LPR: lanes per row; U: chunks a lane keeps in flight per round.
@@ -209,6 +221,25 @@ __global__ __launch_bounds__(1024) void spmv_kernel(SpmvArgs a) {
         live = row < a.M;
     }
     const int rowc = live ? row : a.M - 1;   // clamp: dead lanes load valid memory
+
+    // LSTM: what the epilogue needs from memory is fetched now, ahead of everything else,
+    // so that it does not start with a round trip (these loads are older than the copy of
+    // x, so the wait before the barrier covers them too): the row's bias by the row's first
+    // lane, the unit's cell state by the lane that finishes the unit.
+    // With 16 lanes per row or fewer the four gate rows of a unit sit in one wavefront and
+    // the unit is finished by the first lane of its first row; otherwise through LDS by
+    // lane `local unit number` of the workgroup.
+    constexpr bool kUnitInWave = LSTM && LPR <= 16;
+    float row_bias = 0.f, cell_in = 0.f;
+    if constexpr (LSTM) {
+        if (live) row_bias = a.bias[row];   // gate blocks i, f, g, o = rows (same address per row)
+        if constexpr (kUnitInWave) {
+            if (lane_in_row == 0 && (row_in_wg & 3) == 0 && live) cell_in = a.c_in[row];   // row = unit here
+        } else {
+            const int unit = blockIdx.x * (a.rows_per_wg >> 2) + tid;
+            if (tid < (a.rows_per_wg >> 2) && unit < a.H) cell_in = a.c_in[unit];
+        }
+    }
 
     const VRaw* vrow = reinterpret_cast<const VRaw*>(
         static_cast<const VT*>(a.vals) + (size_t)rowc * a.row_len);
@@ -283,19 +314,34 @@ __global__ __launch_bounds__(1024) void spmv_kernel(SpmvArgs a) {
 
     acc = group_sum<LPR>(acc);
     if constexpr (LSTM) {
-        // the four pre-activations of a unit meet in LDS; one lane per unit finishes it
+        // each gate's nonlinearity is applied in its own row's lanes (the four gates of a
+        // unit in parallel) ...
+        const float pre_act = acc + row_bias;
+        const float act = (row_in_wg & 3) == 2 ? tanh_fast(pre_act) : logistic_fast(pre_act);
+        if constexpr (kUnitInWave) {
+            // ... and the unit's four activations are fetched from their rows' lanes: no LDS
+            // memory, no barrier
+            const int first = (tid & 63) / LPR / 4 * 4 * LPR;    // first lane of the unit's gate i row
+            const float gi = __shfl(act, first, kWave), gf = __shfl(act, first + LPR, kWave);
+            const float gg = __shfl(act, first + 2 * LPR, kWave), go = __shfl(act, first + 3 * LPR, kWave);
+            if (lane_in_row == 0 && (row_in_wg & 3) == 0 && live) {
+                const float c = fmaf(gf, cell_in, gi * gg);
+                a.c_out[row] = c;                                  // row = unit for gate i rows
+                a.h_out[row] = go * tanh_fast(c);
+            }
+            return;
+        }
+        // ... the activations meet in LDS, one lane per unit finishes it
         float* pre = xs + a.pre_off;
-        if (lane_in_row == 0) pre[row_in_wg] = acc;
+        if (lane_in_row == 0) pre[row_in_wg] = act;
         __syncthreads();
         const int unit = blockIdx.x * (a.rows_per_wg >> 2) + tid;
         if (tid < (a.rows_per_wg >> 2) && unit < a.H) {
-            const float gi = logistic(pre[4 * tid + 0] + a.bias[unit]);
-            const float gf = logistic(pre[4 * tid + 1] + a.bias[a.H + unit]);
-            const float gg = tanhf(pre[4 * tid + 2] + a.bias[2 * a.H + unit]);
-            const float go = logistic(pre[4 * tid + 3] + a.bias[3 * a.H + unit]);
-            const float c = fmaf(gf, a.c_in[unit], gi * gg);
+            const float gi = pre[4 * tid + 0], gf = pre[4 * tid + 1];
+            const float gg = pre[4 * tid + 2], go = pre[4 * tid + 3];
+            const float c = fmaf(gf, cell_in, gi * gg);
             a.c_out[unit] = c;
-            a.h_out[unit] = go * tanhf(c);
+            a.h_out[unit] = go * tanh_fast(c);
         }
     } else {
         if (live && lane_in_row == 0) a.y[row] = acc;
