@@ -496,6 +496,17 @@ def main():
             except Exception as exc:             # never lose the headline line
                 extras["lstm_error"] = str(exc)[:200]
 
+        # the paper's own timings of the same layers (Tables 1-3), as context only: another
+        # GPU (an NVIDIA part the paper does not name), trained weights, precision not stated
+        extras["paper_context_us"] = {
+            "hardware": "unnamed NVIDIA GPU (paper, Sec. 4); not a target",
+            "table1_lstm_2x1500": {"dense": 294.1, "balanced_80pct": 120.2},
+            "table2_vgg_fc6_4096x25088": {"dense": 979.9, "balanced_93pct": 231.1},
+            "table2_vgg_fc7_4096x4096": {"dense": 265.5, "balanced_93pct": 70.3},
+            "table3_bilstm_1024": {"dense": 117.9, "balanced_87.5pct": 83.9},
+            "eq5_launch_overhead": 10.0,
+        }
+
         # the other configurations of the metric, same protocol (cold, graph of launches),
         # fewer launches: {us per launch, GB/s of algorithmic bytes, dense baseline us}
         if not args.warm and args.workload == "lstm1500":
