@@ -101,6 +101,32 @@ def region_us(torch, fn, n):
     return s.elapsed_time(e) * 1e3 / n
 
 
+def graph_us(torch, fn, n):
+    """Time per call of n calls captured into one graph and replayed: the protocol of `value`,
+    free of the host's per-call cost (which would inflate kernels of a few microseconds).
+    Falls back to eager launches if the calls cannot be captured."""
+    try:
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            fn(0)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(n):
+                fn(i)
+        g.replay()
+        torch.cuda.synchronize()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        g.replay()
+        e.record()
+        torch.cuda.synchronize()
+        return s.elapsed_time(e) * 1e3 / n
+    except Exception:
+        torch.cuda.synchronize()
+        return region_us(torch, fn, n)
+
+
 OTHER_WORKLOADS = ("tiny", "sweep_k32", "sweep_k16", "sweep_k8", "sweep_k4", "sweep_k2",
                    "lstm1500_n8", "lstm1500_n32", "lstm1500_n128", "fc6_b1", "fc6_b16",
                    # Table 4's axes: balance range 25 / 50 / 100 at 60 % .. 80 % on the LSTM matrix
@@ -168,26 +194,28 @@ def quick_measure(torch, np, bs, workloads, dev, name, o_time, launches=200):
          (lambda i: bs.bs_dense_gemv(Wc[i % len(Wc)], Xd, out=Y))
     for i in range(2):
         fn(i)
-    d_us = region_us(torch, fn, n_d)
+    d_us = graph_us(torch, fn, n_d)
     res["dense_us"] = round(d_us, 1)
     res["speedup_vs_dense"] = round(d_us / us, 2)
     # context: the vendor library's dense product on the same matrix (torch.matmul ->
     # rocBLAS / hipBLASLt; fp16 weights multiply an fp16 copy of X there)
     try:
         Xl = Xd if wl.dtype == "f32" else Xd.half()
-        lib = lambda i: torch.matmul(Wc[i % len(Wc)], Xl)
+        Yl = torch.empty(Y.shape, dtype=Xl.dtype, device=dev)
+        lib = lambda i: torch.matmul(Wc[i % len(Wc)], Xl, out=Yl)
         for i in range(3):
             lib(i)
-        res["dense_library_us"] = round(region_us(torch, lib, n_d), 1)
+        res["dense_library_us"] = round(graph_us(torch, lib, n_d), 1)
         res["speedup_vs_faster_dense"] = round(min(d_us, res["dense_library_us"]) / us, 2)
     except Exception as exc:
         res["dense_library_error"] = str(exc)[:80]
     # eq. (5): the dense time scaled by the kept fraction, launch overhead not scaled
     res["ideal_us_eq5"] = round(max(d_us - o_time, 0.0) * (1 - wl.sparsity) + o_time, 2)
     # pruning + packing this matrix (W rotates as for the dense baseline)
-    pfn = lambda i: bs.bs_prune_pack(Wc[i % len(Wc)], wl.bank, wl.k)
+    p_out = (torch.empty_like(vals), torch.empty_like(idx))
+    pfn = lambda i: bs.bs_prune_pack(Wc[i % len(Wc)], wl.bank, wl.k, out=p_out)
     pfn(0)
-    p_us = region_us(torch, pfn, 6)
+    p_us = graph_us(torch, pfn, 6)
     res["prune_pack_us"] = round(p_us, 1)
     res["prune_pack_GBps"] = round((W.nbytes + wl.nnz * (wl.val_bytes + 1)) / p_us / 1e3, 1)
     return res
@@ -383,7 +411,7 @@ def main():
         def avg_us(fn, n):
             for _ in range(3):
                 fn(0)
-            return region_us(torch, fn, n)
+            return graph_us(torch, fn, n)
 
         # dense baseline on the unpruned-shape matrix, same residency protocol
         dense_bytes = wl.dense_bytes()
@@ -401,7 +429,8 @@ def main():
         o_time = extras.get("launch_floor_us", 0.0)
         extras["ideal_us_eq5"] = round((d_us - o_time) * (1 - wl.sparsity) + o_time, 2)
         # one-time pruning + packing of the dense matrix
-        p_us = avg_us(lambda i: bs.bs_prune_pack(Wd, wl.bank, wl.k), 10)
+        p_out = (torch.empty_like(vals), torch.empty_like(idx))
+        p_us = avg_us(lambda i: bs.bs_prune_pack(Wd, wl.bank, wl.k, out=p_out), 10)
         p_bytes = W.nbytes + wl.nnz * (wl.val_bytes + 1)
         extras["prune_pack_us"] = round(p_us, 1)
         extras["prune_pack_GBps"] = round(p_bytes / p_us / 1e3, 1)
@@ -426,7 +455,7 @@ def main():
         # protocol (a graph of launches): an empty launch, a kernel that only reads this
         # workload's bytes (cold, rotating buffers), and a large streaming read
         try:
-            def graph_us(launch, n):
+            def floor_graph_us(launch, n):
                 side2 = torch.cuda.Stream()
                 with torch.cuda.stream(side2):
                     for i in range(min(n, 8)):
@@ -441,13 +470,13 @@ def main():
                 return region_us(torch, lambda i: gp.replay(), 3) / n
 
             floor = {}
-            floor["empty_launch_us"] = round(graph_us(lambda i: bs.bs_probe_empty(750, 256), 1000), 3)
+            floor["empty_launch_us"] = round(floor_graph_us(lambda i: bs.bs_probe_empty(750, 256), 1000), 3)
             same = (alg_bytes + 15) // 16 * 16
             n_same = max(2, -(-2 * LLC_BYTES // same) + 1)
             bufs = [torch.empty(same, dtype=torch.uint8, device=dev) for _ in range(n_same)]
             for b_ in bufs:
                 b_.fill_(1)
-            t_same = graph_us(lambda i: bs.bs_probe_stream_read(bufs[i % n_same]), 2 * n_same)
+            t_same = floor_graph_us(lambda i: bs.bs_probe_stream_read(bufs[i % n_same]), 2 * n_same)
             floor["stream_read_same_bytes_us"] = round(t_same, 3)
             floor["stream_read_same_bytes_GBps"] = round(same / t_same / 1e3, 1)
             del bufs
@@ -455,7 +484,7 @@ def main():
             bufs = [torch.empty(big, dtype=torch.uint8, device=dev) for _ in range(3)]
             for b_ in bufs:
                 b_.fill_(1)
-            t_big = graph_us(lambda i: bs.bs_probe_stream_read(bufs[i % 3]), 12)
+            t_big = floor_graph_us(lambda i: bs.bs_probe_stream_read(bufs[i % 3]), 12)
             floor["stream_read_288MB_us"] = round(t_big, 2)
             floor["stream_read_288MB_GBps"] = round(big / t_big / 1e3, 1)
             floor["value_over_same_bytes_stream"] = round(t_same / us_per_step, 3)
