@@ -77,6 +77,15 @@ def test_bad_arguments_are_refused_before_launch():
     assert lib.bs_spmv_ex(p, p, 0, 4, 8, 4, 2, p, p, 16, 3, null, null, null) == 3   # 48 lanes per workgroup
     assert lib.bs_dense_gemv(p, 0, 0, 8, p, p, null) == 2
     assert lib.bs_dense_gemm(p, 0, 4, 8, p, 4, 2, p, 4, null) == 2
+    out = (ctypes.c_int64 * 16)()
+    assert lib.bs_spmm_plan(0, 4, 8, 4, 2, 4, None, 16) == 1             # no output array
+    assert lib.bs_spmm_plan(0, 4, 10, 4, 2, 4, out, 16) == 2             # K % bank
+    assert lib.bs_spmm_plan(0, 4, 8, 4, 2, 0, out, 16) == 2              # N < 1
+    assert lib.bs_spmm_plan(5, 4, 8, 4, 2, 4, out, 16) == 3              # dtype
+    # LSTM step and pruning round: shape rules of their own
+    assert lib.bs_lstm_step(p, p, 0, 6, 8, 2, 1, p, p, p, p, p, p, null) == 3       # H % 4
+    assert lib.bs_lstm_step(p, p, 0, 8, 8, 2, 1, p, p, p, p, p, p, null) == 3       # h_out == h_in
+    assert lib.bs_reprune(p, p, 0, 4, 8, 4, 2, 3, p, p, null) == 2                  # k2 > k
 
 
 def _plan_invariants(b, dtype, M, K, bank, k, N):
