@@ -489,6 +489,16 @@ def main():
             floor["stream_read_288MB_GBps"] = round(big / t_big / 1e3, 1)
             floor["value_over_same_bytes_stream"] = round(t_same / us_per_step, 3)
             del bufs
+            # what an LDS gather costs (the SpMM kernels' inner loop): 256 workgroups of 768
+            # lanes that only issue 16-byte LDS reads; ns per wavefront read and compute unit
+            reads, thr = 16000, 768
+            t0 = floor_graph_us(lambda i: bs.bs_probe_lds_gather(thr, 0, 16, 8), 4)   # fill + launch only
+            lds = {}
+            for key, pattern, lanes in (("adjacent_1KB", 0, 16), ("rows_of_256B", 1, 16),
+                                        ("rows_of_128B", 1, 8), ("rows_of_64B", 1, 4), ("rows_of_32B", 1, 2)):
+                t = floor_graph_us(lambda i: bs.bs_probe_lds_gather(thr, pattern, lanes, reads), 4)
+                lds[key] = round((t - t0) * 1e3 / ((reads - 8) * thr / 64), 3)
+            floor["lds_gather_ns_per_wavefront_read_per_cu"] = lds
             extras["machine_floor"] = floor
         except Exception as exc:                 # never lose the headline line
             extras["machine_floor_error"] = str(exc)[:200]

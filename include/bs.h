@@ -208,10 +208,22 @@ int bs_dense_gemm(const void* W, int dtype, int64_t M, int64_t K,
  *                       at least 16) from DEVICE `src`, 16 bytes per lane and load, and
  *                       stores nothing; `sink` is DEVICE memory of at least 256 bytes
  *                       that is never written for real data (may be NULL).
- * Both enqueue on `stream` like every other call.
+ * bs_probe_lds_gather   256 workgroups of `threads` lanes (64..1024, a multiple of 64) fill
+ *                       120 KB of LDS and then issue `reads` (a multiple of 8) 16-byte LDS
+ *                       reads per lane and nothing else: the gather rate the SpMM kernels
+ *                       live on.  pattern 0: a wavefront reads 1 KB of adjacent bytes;
+ *                       pattern 1: groups of `group_lanes` (2, 4, 8 or 16) neighbouring lanes
+ *                       read adjacent 16-byte pieces of one row of group_lanes*16 bytes,
+ *                       every group a random row (the rows of X that the entries of
+ *                       different matrix rows point at).  `sink` as above.
+ *                       Time per wavefront read and compute unit = kernel time /
+ *                       (reads * threads / 64).
+ * All enqueue on `stream` like every other call.
  */
 int bs_probe_empty(int grid, int threads, void* stream);
 int bs_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream);
+int bs_probe_lds_gather(int threads, int pattern, int group_lanes, int reads, void* sink,
+                        void* stream);
 
 #ifdef __cplusplus
 }

@@ -22,6 +22,7 @@ EXPORTS = (
     "bs_nnz", "bs_vals_bytes", "bs_idx_bytes", "bs_status_str", "bs_prune_pack", "bs_spmv",
     "bs_spmv_ex", "bs_spmm_workspace_bytes", "bs_spmm_plan", "bs_spmm", "bs_dense_gemv", "bs_dense_gemm",
     "bs_lstm_step", "bs_lstm_sequence", "bs_reprune", "bs_probe_empty", "bs_probe_stream_read",
+    "bs_probe_lds_gather",
 )
 
 
@@ -69,12 +70,13 @@ def load_library():
     lib.bs_dense_gemm.argtypes = [vp, i32, i64, i64, vp, i64, i64, vp, i64, vp]
     lib.bs_probe_empty.argtypes = [i32, i32, vp]
     lib.bs_probe_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.bs_probe_lds_gather.argtypes = [i32, i32, i32, i32, vp, vp]
     lib.bs_reprune.argtypes = [vp, vp, i32, i64, i64, i32, i32, i32, vp, vp, vp]
     lib.bs_lstm_step.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.bs_lstm_sequence.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, vp, vp, vp, vp, vp]
     for name in ("bs_prune_pack", "bs_spmv", "bs_spmv_ex", "bs_spmm", "bs_dense_gemv",
                  "bs_dense_gemm", "bs_lstm_step", "bs_lstm_sequence", "bs_reprune", "bs_probe_empty",
-                 "bs_probe_stream_read"):
+                 "bs_probe_stream_read", "bs_probe_lds_gather"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -385,3 +387,10 @@ def bs_probe_stream_read(src: torch.Tensor, sink: torch.Tensor = None):
     nbytes = src.numel() * src.element_size()
     _check(load_library().bs_probe_stream_read(_ptr(src), nbytes, _ptr(sink), _stream()),
            "bs_probe_stream_read")
+
+
+def bs_probe_lds_gather(threads: int = 768, pattern: int = 1, group_lanes: int = 8, reads: int = 16000):
+    """Measurement helper: 256 workgroups that only issue 16-byte LDS reads (`reads` per lane);
+    pattern 0 = adjacent bytes, 1 = groups of `group_lanes` lanes on random rows."""
+    _check(load_library().bs_probe_lds_gather(threads, pattern, group_lanes, reads, None, _stream()),
+           "bs_probe_lds_gather")

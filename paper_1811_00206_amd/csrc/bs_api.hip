@@ -55,6 +55,21 @@ int bs_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream
     return bs::launch_probe_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream));
 }
 
+int bs_probe_lds_gather(int threads, int pattern, int group_lanes, int reads, void* sink,
+                        void* stream) {
+    if (threads < 64 || threads > 1024 || threads % 64 || reads < 8 || reads % 8) return BS_ERR_SHAPE;
+    if (pattern != 0 && pattern != 1) return BS_ERR_SHAPE;
+    int shift = 4;
+    if (pattern == 1) {
+        if (group_lanes != 2 && group_lanes != 4 && group_lanes != 8 && group_lanes != 16)
+            return BS_ERR_SHAPE;
+        shift = group_lanes == 2 ? 1 : group_lanes == 4 ? 2 : group_lanes == 8 ? 3 : 4;
+    }
+    if (sink && !aligned16(sink)) return BS_ERR_ALIGN;
+    return bs::launch_probe_lds_gather(threads, pattern, shift, reads, sink,
+                                       static_cast<hipStream_t>(stream));
+}
+
 const char* bs_status_str(int status) {
     switch (status) {
         case BS_OK: return "ok";

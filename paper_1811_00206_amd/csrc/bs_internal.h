@@ -40,6 +40,8 @@ int launch_dense_gemm(const void* W, int dtype, int64_t M, int64_t K, const floa
 // measurement helpers (bs_probe.hip)
 int launch_probe_empty(int grid, int threads, hipStream_t st);
 int launch_probe_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st);
+int launch_probe_lds_gather(int threads, int pattern, int group_shift, int reads, void* sink,
+                            hipStream_t st);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? BS_OK : BS_ERR_HIP; }
 

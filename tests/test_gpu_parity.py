@@ -413,6 +413,14 @@ def test_measurement_helpers_run_and_refuse_bad_sizes():
         bs.bs_probe_empty(0, 256)
     with pytest.raises(bs.BsError):
         bs.bs_probe_empty(4, 100)
+    bs.bs_probe_lds_gather(256, 0, 16, 64)
+    bs.bs_probe_lds_gather(768, 1, 8, 64)
+    bs.bs_probe_lds_gather(1024, 1, 2, 8)
+    torch.cuda.synchronize()
+    with pytest.raises(bs.BsError):
+        bs.bs_probe_lds_gather(768, 1, 3, 64)        # group of lanes not 2, 4, 8 or 16
+    with pytest.raises(bs.BsError):
+        bs.bs_probe_lds_gather(768, 1, 8, 60)        # reads not a multiple of 8
 
 
 def test_device_side_argument_errors():
