@@ -451,7 +451,7 @@ def main():
                                            (wl.val_bytes + 1) / r_us / 1e3, 1)
         ev.close()
 
-        # the machine's floor, measured with the library's two helper kernels in the same
+        # the machine's floor, measured with the library's helper kernels in the same
         # protocol (a graph of launches): an empty launch, a kernel that only reads this
         # workload's bytes (cold, rotating buffers), and a large streaming read
         try:
