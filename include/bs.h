@@ -99,6 +99,9 @@ int bs_reprune(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64
  * fp32 multiply-add, fp32 accumulation (binary16 vals are widened exactly).
  * The summation order is fixed for a given shape, so results are
  * bit-reproducible from call to call.
+ * x is staged in the LDS of every compute unit (Sec. 3.4: the dense vector in shared
+ * memory); above K = 40960 (160 KB) it is walked in slabs of whole banks by a slower,
+ * general kernel.
  */
 int bs_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K,
             int bank, int k, const float* x, float* y, void* stream);
@@ -109,7 +112,8 @@ int bs_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t 
  *                  0 = choose from the shape (what bs_spmv does)
  *   rows_per_wg    rows handled by one workgroup; lanes_per_row*rows_per_wg must
  *                  be a multiple of 64 and at most 1024; 0 = choose
- * Invalid combinations return BS_ERR_UNSUPPORTED.
+ * Invalid combinations return BS_ERR_UNSUPPORTED, and so does any non-zero shape when
+ * K > 40960 (the slab kernel has one shape).
  *   start_event, stop_event  optional hipEvent_t handles (NULL = none) that
  *                  receive the kernel's own begin and end time stamps on the
  *                  GPU, so one launch can be timed without the gaps between

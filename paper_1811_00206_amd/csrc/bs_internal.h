@@ -23,6 +23,10 @@ int launch_reprune(const void* vals, const uint8_t* idx, int dtype, int64_t n_ba
 int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
                 int k, const float* x, float* y, int lanes_per_row, int rows_per_wg,
                 hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st);
+// the same product for x larger than one compute unit's LDS (bs_spmv_slab.hip)
+int launch_spmv_slabbed(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K,
+                        int bank, int k, const float* x, float* y, hipEvent_t ev_start,
+                        hipEvent_t ev_stop, hipStream_t st);
 // fused LSTM step: the matrix is 4H x (I + H); see bs_lstm_step in bs.h
 int launch_lstm_step(const void* vals, const uint8_t* idx, int dtype, int64_t H, int64_t I, int bank,
                      int k, const float* x, const float* h_in, const float* bias,

@@ -23,8 +23,13 @@ int launch_common(const void* vals, const uint8_t* idx, int dtype, int64_t M, in
     // LDS: x, then (if it fits) one word per row entry for the bank table
     const size_t x_floats = ((size_t)K + 3) / 4 * 4;
     size_t lds = x_floats * sizeof(float);
-    if (lds > (size_t)kMaxLdsBytes) return BS_ERR_UNSUPPORTED;   // x must fit in one CU's LDS
     if (M > INT32_MAX) return BS_ERR_UNSUPPORTED;
+    if (lds > (size_t)kMaxLdsBytes) {
+        // x does not fit one compute unit's LDS: the slab-by-slab kernel (no launch-shape
+        // overrides, no fused LSTM step there)
+        if (lstm || lanes_per_row != 0 || rows_per_wg != 0) return BS_ERR_UNSUPPORTED;
+        return launch_spmv_slabbed(vals, idx, dtype, M, K, bank, k, x, y, ev_start, ev_stop, st);
+    }
     int table_off = 0;
     if (lds + (size_t)row_len * 4 <= (size_t)kMaxLdsBytes) {
         table_off = (int)x_floats;

@@ -185,12 +185,39 @@ def test_spmv_largest_x_that_fits_lds_and_beyond():
     v, i = bs_ref.prune_pack(W, 256, 3)
     y = host(bs.bs_spmv(dev(v), dev(i), 256, dev(x)))
     assert bs_ref.rel_l2(y, bs_ref.spmv(v, i, 256, x)) <= 1e-5
+    # one bank more: x no longer fits, the product walks x in slabs
     K2 = K + 256
-    v2 = torch.zeros((2, K2 // 256, 3), dtype=torch.float32, device=DEV)
-    i2 = torch.zeros((2, K2 // 256, 3), dtype=torch.uint8, device=DEV)
+    say("spmv K", K2)
+    W2 = workloads.draw_weights(48, K2, 1.0, "f32", 35)
+    x2 = workloads.draw_activations(K2, 1, 35)
+    v2, i2 = bs_ref.prune_pack(W2, 256, 3)
+    y2 = host(bs.bs_spmv(dev(v2), dev(i2), 256, dev(x2)))
+    assert bs_ref.rel_l2(y2, bs_ref.spmv(v2, i2, 256, x2)) <= 1e-5
+    # ... but neither launch-shape overrides nor the fused LSTM step exist there
     with pytest.raises(bs.BsError) as e:
-        bs.bs_spmv(v2, i2, 256, torch.zeros(K2, device=DEV))
+        bs.bs_spmv_ex(dev(v2), dev(i2), 256, dev(x2), 64, 4)
     assert e.value.status == 3
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("M,K,bank,k,dtype", [
+    (70, 65536, 256, 16, "f32"),          # 4 slabs of whole banks, 16-byte chunks
+    (133, 50000, 100, 7, "f32"),          # chunks of 4 entries cross banks; ragged last slab
+    (5, 49152, 64, 3, "f16"),             # 8-entry chunks: slabs of a multiple of 8 banks
+    (9, 41003, 131, 5, "f32"),            # odd everything: 1-entry chunks, K % 4 != 0
+    (1, 262144, 256, 256, "f16"),         # one dense row of 512 KB of x
+    (300, 81920, 2, 1, "f32"),            # 40960 banks of two
+])
+def test_spmv_x_larger_than_lds(M, K, bank, k, dtype):
+    say("spmv slabs", M, K, bank, k, dtype)
+    W = workloads.draw_weights(M, K, 1.0, dtype, 36)
+    x = workloads.draw_activations(K, 1, 36)
+    v, i = bs_ref.prune_pack(W, bank, k)
+    y = host(bs.bs_spmv(dev(v), dev(i), bank, dev(x)))
+    Wp = bs_ref.unpack(v, i, bank).astype(np.float64)
+    scale = (np.abs(Wp) @ np.abs(x.astype(np.float64))).max() + 1e-300
+    assert np.abs(y - bs_ref.spmv(v, i, bank, x)).max() <= 1e-5 * scale
+    assert bs_ref.rel_l2(y, bs_ref.spmv(v, i, bank, x)) <= (1e-5 if M > 8 else 1e-4)
 
 
 # ------------------------------------------------------------------- SpMM
