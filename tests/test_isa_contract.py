@@ -20,7 +20,7 @@ import pytest
 from paper_1811_00206_amd import build as bs_build
 
 SOURCES = ["bs_spmv_f32.hip", "bs_spmv_f16.hip", "bs_spmm_f32.hip", "bs_spmm_f16.hip",
-           "bs_spmm_rows.hip"]
+           "bs_spmm_rows.hip", "bs_spmv_slab.hip"]
 
 
 def _assembly(src):
