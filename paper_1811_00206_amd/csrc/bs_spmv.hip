@@ -52,12 +52,12 @@ int launch_common(const void* vals, const uint8_t* idx, int dtype, int64_t M, in
         while (lpr < 64 && (cpr + lpr - 1) / lpr > 4) lpr <<= 1;
     }
     if (lpr < 1 || lpr > 64 || (lpr & (lpr - 1))) return BS_ERR_UNSUPPORTED;
-    // chunk slots per lane and round: 2, 3, 4, 6 or 8 (3: the 6000 x 3000 matrix with 32 lanes
-    // per row; a fourth, empty slot cost 0.06 of its 3.98 us)
+    // chunk slots per lane and round: as many as the row needs, 2..8 (a slot that is empty for
+    // every lane still costs its two loads: 0.06 of 3.98 us on the 6000 x 3000 matrix, which
+    // needs 3; 1-3 % on the shapes that need 5)
     int64_t need = (cpr + lpr - 1) / lpr;
-    int u = need >= kMaxInFlight ? kMaxInFlight : (int)((need + 1) / 2 * 2);
+    int u = need >= kMaxInFlight ? kMaxInFlight : (int)need;
     if (u < 2) u = 2;
-    if (need == 3) u = 3;
     if (lstm) u = u <= 4 ? 4 : 8;
 
     int rpw = rows_per_wg;

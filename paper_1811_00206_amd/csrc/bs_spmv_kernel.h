@@ -382,7 +382,9 @@ int spmv_launch_u(int u, const SpmvArgs& a, const SpmvLaunch& l) {
         case 2: return spmv_launch_one<VT, CH, LPR, 2>(a, l);
         case 3: return spmv_launch_one<VT, CH, LPR, 3>(a, l);
         case 4: return spmv_launch_one<VT, CH, LPR, 4>(a, l);
+        case 5: return spmv_launch_one<VT, CH, LPR, 5>(a, l);
         case 6: return spmv_launch_one<VT, CH, LPR, 6>(a, l);
+        case 7: return spmv_launch_one<VT, CH, LPR, 7>(a, l);
         case 8: return spmv_launch_one<VT, CH, LPR, 8>(a, l);
     }
     return BS_ERR_UNSUPPORTED;

@@ -76,10 +76,10 @@ def kernels(texts):
 
 
 def test_every_instantiation_is_present(kernels):
-    # 3 chunk widths for fp32 + 4 for fp16, 7 group widths; 5 in-flight depths for
+    # 3 chunk widths for fp32 + 4 for fp16, 7 group widths; 7 in-flight depths for
     # SpMV, plus 4 group widths and 2 depths of the fused LSTM step; 5 group widths
     # and 2 depths for SpMM
-    assert sum("spmv_kernel" in n for n in kernels) == (3 + 4) * 7 * 5 + (3 + 4) * 4 * 2
+    assert sum("spmv_kernel" in n for n in kernels) == (3 + 4) * 7 * 7 + (3 + 4) * 4 * 2
     assert sum("spmm_kernel" in n for n in kernels) == (3 + 4) * 5 * 2
     # one lane per (row, column group): chunk widths only
     assert sum("spmm_rows_kernel" in n for n in kernels) == 3 + 4
