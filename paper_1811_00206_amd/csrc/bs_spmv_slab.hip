@@ -118,7 +118,8 @@ int launch_spmv_slabbed(const void* vals, const uint8_t* idx, int dtype, int64_t
     // every slab's run starts and ends on a chunk boundary
     int ch = 16 / vsize;
     while (ch > 1 && row_len % ch != 0) ch >>= 1;
-    int64_t sb = (int64_t)kMaxLdsBytes / (4 * ((int64_t)bank + k));   // slab of x + its table
+    // slab of x (rounded up to 16 bytes) + its table
+    int64_t sb = ((int64_t)kMaxLdsBytes - 16) / (4 * ((int64_t)bank + k));
     if (sb > nb) sb = nb;
     for (;;) {
         const int step = ch / gcd_int(k, ch);

@@ -207,6 +207,7 @@ def test_spmv_largest_x_that_fits_lds_and_beyond():
     (9, 41003, 131, 5, "f32"),            # odd everything: 1-entry chunks, K % 4 != 0
     (1, 262144, 256, 256, "f16"),         # one dense row of 512 KB of x
     (300, 81920, 2, 1, "f32"),            # 40960 banks of two
+    (17, 89030, 2, 1, "f16"),             # slab and table fill LDS to the last 16 bytes
 ])
 def test_spmv_x_larger_than_lds(M, K, bank, k, dtype):
     say("spmv slabs", M, K, bank, k, dtype)
