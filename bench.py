@@ -11,13 +11,14 @@ banks of 100 keeping 10 (90 % sparse), batch 1.
 The timed region is exactly K steps between two HIP events on the launch
 stream; ``value`` and ``roofline.achieved`` are both algorithmic bytes x K /
 that wall time (gaps between launches included, so the kernel's own duration is
-at most this).  A second pass over the same K launches attaches a pair of
-events to every launch, which receive that kernel's own begin/end time stamps;
-its statistics are reported under ``extras`` (that method cannot report less
-than about 3.9 us, the figure it gives for an empty kernel).
-"Cold" (default) rotates over enough copies of vals/idx to exceed twice the
-256 MB last-level cache, so every launch streams from HBM; ``--warm`` reuses one
-copy (cache resident; reported as such, never as HBM bandwidth).
+at most this).
+"Cold" (default): the launches rotate over enough copies of vals/idx to exceed
+twice the 256 MB last-level cache, and a 768 MB streaming read of unrelated
+memory is enqueued right before every timed replay, so no timed launch finds its
+matrix in a cache whatever K is; ``config.residency`` states the bytes the timed
+launches touch.  ``--warm`` reuses one copy (cache resident; reported as such,
+never as HBM bandwidth).  The machine's floor for the same bytes (a kernel that
+only reads them, same protocol, same run) is reported inside ``roofline``.
 
 Prints ONE JSON line on stdout.
 """
@@ -36,12 +37,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 LLC_BYTES = 256 << 20
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/);
-# None until measured for that workload.
+EVICT_BYTES = 768 << 20
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (the two commands
+# and the copy-kernel calibration are in profiles/spmv_lstm1500_hbm_traffic.md).  A figure
+# belongs to one kernel instantiation; it is reported only while bs_spmv_plan still names
+# that instantiation for the workload.
 MEASURED_TRAFFIC = {
-    # profiles/spmv_lstm1500_hbm_traffic.md: 4496.8 KiB fetched x 1.993 (copy-kernel
-    # calibration) + 23.4 KiB written
-    ("lstm1500", "cold"): 9_252_196,
+    ("lstm1500", "cold"): {"kernel": "spmv_kernel<float,4,32,3>", "bytes": 9_252_196},
 }
 
 
@@ -55,6 +57,8 @@ def parse():
     ap.add_argument("--eager", action="store_true", help="time Python-side launches, no HIP graph")
     ap.add_argument("--no-extras", action="store_true", help="skip the secondary measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--only", default="", help="comma-separated other workloads to measure under extras "
+                                               "(default: all of them)")
     return ap.parse_args()
 
 
@@ -101,10 +105,27 @@ def region_us(torch, fn, n):
     return s.elapsed_time(e) * 1e3 / n
 
 
-def graph_us(torch, fn, n):
-    """Time per call of n calls captured into one graph and replayed: the protocol of `value`,
-    free of the host's per-call cost (which would inflate kernels of a few microseconds).
-    Falls back to eager launches if the calls cannot be captured."""
+EAGER_FALLBACKS = []     # what had to be timed as eager launches (reported under extras)
+
+
+class Evictor:
+    """A streaming read of EVICT_BYTES of unrelated memory (three times the last-level cache).
+    Enqueued right before a timed replay, on the same stream, it leaves neither L2 nor the
+    last-level cache holding anything the replay is about to read; reads leave no dirty lines
+    behind, so the timed region does not pay for write-backs either."""
+
+    def __init__(self, torch, probe, dev):
+        self.buf = torch.empty(EVICT_BYTES, dtype=torch.uint8, device=dev)
+        self.buf.fill_(1)
+        self.probe = probe
+
+    def __call__(self):
+        self.probe.probe_stream_read(self.buf)
+
+
+def capture(torch, fn, n, what):
+    """n calls of fn captured into one graph (after an eager warm-up call on a side stream) and
+    replayed once, untimed.  None if the calls cannot be captured (recorded in EAGER_FALLBACKS)."""
     try:
         side = torch.cuda.Stream()
         with torch.cuda.stream(side):
@@ -116,15 +137,35 @@ def graph_us(torch, fn, n):
                 fn(i)
         g.replay()
         torch.cuda.synchronize()
-        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        s.record()
-        g.replay()
-        e.record()
+        return g
+    except Exception as exc:
         torch.cuda.synchronize()
-        return s.elapsed_time(e) * 1e3 / n
-    except Exception:
-        torch.cuda.synchronize()
+        EAGER_FALLBACKS.append(f"{what}: {str(exc)[:120]}")
+        print(f"bench.py: graph capture failed for {what!r} ({exc}); timing eager launches",
+              file=sys.stderr)
+        return None
+
+
+def timed_replay_us(torch, g, n, evict=None):
+    """One replay of a captured graph of n calls between two events; `evict` is enqueued first."""
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    if evict is not None:
+        evict()
+    s.record()
+    g.replay()
+    e.record()
+    torch.cuda.synchronize()
+    return s.elapsed_time(e) * 1e3 / n
+
+
+def graph_us(torch, fn, n, what, evict=None):
+    """Time per call of n calls captured into one graph and replayed: the protocol of `value`,
+    free of the host's per-call cost (which would inflate kernels of a few microseconds)."""
+    g = capture(torch, fn, n, what)
+    if g is None:
         return region_us(torch, fn, n)
+    return timed_replay_us(torch, g, n, evict)
 
 
 OTHER_WORKLOADS = ("tiny", "sweep_k32", "sweep_k16", "sweep_k8", "sweep_k4", "sweep_k2",
@@ -134,13 +175,18 @@ OTHER_WORKLOADS = ("tiny", "sweep_k32", "sweep_k16", "sweep_k8", "sweep_k4", "sw
                    "lstm1500_b50_k10", "lstm1500_b100_k40", "lstm1500_b100_k30", "lstm1500_b100_k20",
                    "bilstm1024",
                    # Sec. 4.2: convolution layers as products over im2col columns
-                   "conv5_n196", "conv4_n784", "conv2_n12544",
+                   "conv5_n196", "conv4_n784", "conv2_n12544", "conv1_n50176",
                    # Sec. 4.1's matrix shape, 50 % .. 97 % sparse, batch 1 and 8
                    "bench16k_k128", "bench16k_k64", "bench16k_k32", "bench16k_k16", "bench16k_k8",
                    "bench16k_k128_n8", "bench16k_k32_n8", "bench16k_k8_n8")
 
 
-def quick_measure(torch, np, bs, workloads, dev, name, o_time, launches=200):
+def rotation(alg_bytes):
+    """Copies of a buffer of alg_bytes needed to exceed twice the last-level cache."""
+    return max(2, -(-2 * LLC_BYTES // alg_bytes) + 1)
+
+
+def quick_measure(torch, np, bs, workloads, dev, name, o_time, evict, launches=200):
     """One workload, cold, `launches` graph-replayed launches: time per launch.
     o_time = measured launch floor, for eq. (5)'s ideal time."""
     wl, W, X = workloads.make(name)
@@ -148,77 +194,67 @@ def quick_measure(torch, np, bs, workloads, dev, name, o_time, launches=200):
     Xd = torch.from_numpy(np.ascontiguousarray(X)).to(dev)
     vals, idx = bs.bs_prune_pack(Wd, wl.bank, wl.k)
     alg = wl.spmv_bytes()
-    R = max(2, -(-2 * LLC_BYTES // alg) + 1)
+    R = rotation(alg)
     copies = [(vals, idx)] + [(vals.clone(), idx.clone()) for _ in range(R - 1)]
     spmm = wl.N > 1
     Y = torch.empty((wl.M, wl.N) if spmm else (wl.M,), dtype=torch.float32, device=dev)
     if spmm:
         code = bs.BS_F16 if wl.dtype == "f16" else bs.BS_F32
-        ws = torch.empty(max(16, bs.bs_spmm_workspace_bytes(code, wl.M, wl.K, wl.bank, wl.k, wl.N)),
+        ws = torch.zeros(max(16, bs.bs_spmm_workspace_bytes(code, wl.M, wl.K, wl.bank, wl.k, wl.N)),
                          dtype=torch.uint8, device=dev)
-
-    def launch_all():
-        if spmm:
-            for i in range(launches):
-                v, ix = copies[i % R]
-                bs.bs_spmm(v, ix, wl.bank, Xd, out=Y, workspace=ws)
-        else:
-            cs = [bs.PreparedSpmv(v, ix, wl.bank, Xd, Y) for v, ix in copies]
-            for i in range(launches):
-                cs[i % R]()
-
-    side = torch.cuda.Stream()
-    with torch.cuda.stream(side):
-        launch_all()                                  # warm-up outside any graph
-    torch.cuda.synchronize()
-    g = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(g):
-        launch_all()
-    g.replay()
-    torch.cuda.synchronize()
-    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    s.record()
-    g.replay()
-    e.record()
-    torch.cuda.synchronize()
-    us = s.elapsed_time(e) * 1e3 / launches
+        fn = lambda i: bs.bs_spmm(copies[i % R][0], copies[i % R][1], wl.bank, Xd, out=Y, workspace=ws)
+    else:
+        cs = [bs.PreparedSpmv(v, ix, wl.bank, Xd, Y) for v, ix in copies]
+        fn = lambda i: cs[i % R]()
+    us = graph_us(torch, fn, launches, name, evict)
     res = {"us": round(us, 2), "GBps": round(alg / us / 1e3, 1),
            "frac_of_8TBps": round(alg / us / 1e3 / HBM_PEAK_GBS, 3)}
     if spmm:
         res["TFLOPs"] = round(wl.flops() / us / 1e6, 2)
-    # dense baseline, cold as well
-    Rd = max(2, -(-2 * LLC_BYTES // wl.dense_bytes()) + 1)
+    # dense baselines, cold as well: the hand-written kernel and, as context, the vendor
+    # library's dense product on the same matrix (torch.matmul -> rocBLAS / hipBLASLt; fp16
+    # weights multiply an fp16 copy of X there).  The speedup printed first is against the
+    # faster of the two.
+    Rd = rotation(wl.dense_bytes())
     Wc = [Wd] + [Wd.clone() for _ in range(min(Rd, 8) - 1)]
     n_d = 10 if spmm else 50
-    fn = (lambda i: bs.bs_dense_gemm(Wc[i % len(Wc)], Xd, out=Y)) if spmm else \
-         (lambda i: bs.bs_dense_gemv(Wc[i % len(Wc)], Xd, out=Y))
-    for i in range(2):
-        fn(i)
-    d_us = graph_us(torch, fn, n_d)
-    res["dense_us"] = round(d_us, 1)
-    res["speedup_vs_dense"] = round(d_us / us, 2)
-    # context: the vendor library's dense product on the same matrix (torch.matmul ->
-    # rocBLAS / hipBLASLt; fp16 weights multiply an fp16 copy of X there)
+    dfn = (lambda i: bs.bs_dense_gemm(Wc[i % len(Wc)], Xd, out=Y)) if spmm else \
+          (lambda i: bs.bs_dense_gemv(Wc[i % len(Wc)], Xd, out=Y))
+    d_us = graph_us(torch, dfn, n_d, name + " dense", evict)
+    lib_us = None
     try:
         Xl = Xd if wl.dtype == "f32" else Xd.half()
         Yl = torch.empty(Y.shape, dtype=Xl.dtype, device=dev)
         lib = lambda i: torch.matmul(Wc[i % len(Wc)], Xl, out=Yl)
         for i in range(3):
             lib(i)
-        res["dense_library_us"] = round(graph_us(torch, lib, n_d), 1)
-        res["speedup_vs_faster_dense"] = round(min(d_us, res["dense_library_us"]) / us, 2)
+        lib_us = graph_us(torch, lib, n_d, name + " dense (vendor library)", evict)
     except Exception as exc:
         res["dense_library_error"] = str(exc)[:80]
+    res["speedup_vs_faster_dense"] = round(min(d_us, lib_us if lib_us else d_us) / us, 2)
+    res["dense_us"] = round(d_us, 1)
+    if lib_us:
+        res["dense_library_us"] = round(lib_us, 1)
+    res["speedup_vs_own_dense"] = round(d_us / us, 2)
     # eq. (5): the dense time scaled by the kept fraction, launch overhead not scaled
     res["ideal_us_eq5"] = round(max(d_us - o_time, 0.0) * (1 - wl.sparsity) + o_time, 2)
     # pruning + packing this matrix (W rotates as for the dense baseline)
     p_out = (torch.empty_like(vals), torch.empty_like(idx))
     pfn = lambda i: bs.bs_prune_pack(Wc[i % len(Wc)], wl.bank, wl.k, out=p_out)
-    pfn(0)
-    p_us = graph_us(torch, pfn, 6)
+    p_us = graph_us(torch, pfn, 6, name + " prune_pack", evict)
     res["prune_pack_us"] = round(p_us, 1)
     res["prune_pack_GBps"] = round((W.nbytes + wl.nnz * (wl.val_bytes + 1)) / p_us / 1e3, 1)
     return res
+
+
+def spmv_kernel_name(bs, wl):
+    """The instantiation bs_spmv launches for this workload, as the profiles name it."""
+    code = bs.BS_F16 if wl.dtype == "f16" else bs.BS_F32
+    p = bs.bs_spmv_plan(code, wl.M, wl.K, wl.bank, wl.k)
+    if p["slab_kernel"]:
+        return "spmv_slab_kernel", p
+    vt = "__half" if wl.dtype == "f16" else "float"
+    return f"spmv_kernel<{vt},{p['ch']},{p['lpr']},{p['u']}>", p
 
 
 def main():
@@ -233,9 +269,10 @@ def main():
     import torch
 
     from paper_1811_00206_amd import binding as bs
+    from paper_1811_00206_amd import probe
     from paper_1811_00206_amd import workloads
 
-    if not os.path.exists(bs.library_path()):
+    if not os.path.exists(bs.library_path()) or not os.path.exists(probe.library_path()):
         from paper_1811_00206_amd.build import build_library
         build_library()
     if not torch.cuda.is_available():
@@ -243,6 +280,7 @@ def main():
         return 2
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    bs.bs_init()
 
     wl, W, X = workloads.make(args.workload)
     K, W_steps = args.steps, args.warmup
@@ -252,31 +290,27 @@ def main():
     torch.cuda.synchronize()
 
     alg_bytes = wl.spmv_bytes()
-    if args.warm:
-        R = 1
-    else:
-        R = max(2, -(-2 * LLC_BYTES // alg_bytes) + 1)
+    R = 1 if args.warm else rotation(alg_bytes)
     copies = [(vals, idx)] + [(vals.clone(), idx.clone()) for _ in range(R - 1)]
+    evict = None if args.warm else Evictor(torch, probe, dev)
     spmm = wl.N > 1
     if spmm:
         Y = torch.empty((wl.M, wl.N), dtype=torch.float32, device=dev)
         ws_bytes = bs.bs_spmm_workspace_bytes(bs.BS_F16 if wl.dtype == "f16" else bs.BS_F32,
                                               wl.M, wl.K, wl.bank, wl.k, wl.N)
-        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+        ws = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+        kernel_name, plan = "bs_spmm", {}
     else:
         Y = torch.empty(wl.M, dtype=torch.float32, device=dev)
+        kernel_name, plan = spmv_kernel_name(bs, wl)
 
-    events = None if spmm else HipEvents(K)
     # arguments marshalled once per matrix copy: a step is then one C-ABI call
     calls = None if spmm else [bs.PreparedSpmv(v, ix, wl.bank, Xd, Y) for v, ix in copies]
 
-    def step(i, timed=False):
+    def step(i):
         if spmm:
             v, ix = copies[i % R]
             bs.bs_spmm(v, ix, wl.bank, Xd, out=Y, workspace=ws)
-        elif timed:
-            a, b = events.pairs[i]
-            calls[i % R](a, b)
         else:
             calls[i % R]()
 
@@ -284,57 +318,81 @@ def main():
         step(i)
     torch.cuda.synchronize()
 
-    # ---- timed region A: exactly K steps between two events on the launch stream.
+    # ---- the timed region: exactly K steps between two events on the launch stream.
     # The K launches are captured once into a HIP graph (the deployment form of a
-    # launch-bound loop) and replayed inside the region; --eager launches them
-    # from Python instead.
+    # launch-bound loop), replayed once untimed, and replayed inside the region; --eager
+    # launches them from Python instead.  Cold runs enqueue the evicting read right before
+    # the first event, so the K launches start with empty caches and (rotating over R
+    # copies) never come back to a copy before 2 x the last-level cache has gone by.
     mode = "eager"
-    graph = None
-    if not args.eager:
-        try:
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                if spmm:
-                    for i in range(K):
-                        step(i)
-                else:
-                    gcalls = [bs.PreparedSpmv(v, ix, wl.bank, Xd, Y) for v, ix in copies]
-                    for i in range(K):
-                        gcalls[i % R]()
-            graph.replay()                       # one untimed replay
-            torch.cuda.synchronize()
-            mode = "hip graph of K launches"
-        except Exception as exc:                 # capture unsupported: say so, time eagerly
-            print(f"bench.py: graph capture failed ({exc}); timing eager launches", file=sys.stderr)
-            graph = None
+    graph = None if args.eager else capture(torch, step, K, "headline")
     t_wall0 = time.perf_counter()
     if graph is not None:
-        s_ev, e_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        s_ev.record()
-        graph.replay()
-        e_ev.record()
-        torch.cuda.synchronize()
-        us_per_step = s_ev.elapsed_time(e_ev) * 1e3 / K
+        mode = "hip graph of K launches"
+        us_per_step = timed_replay_us(torch, graph, K, evict)
     else:
+        if evict is not None:
+            evict()
         us_per_step = region_us(torch, step, K)
     t_wall = time.perf_counter() - t_wall0
+    # the same region a few more times (extras): how far one sample of K steps can be off
+    trials = []
+    if graph is not None and not args.no_extras:
+        trials = [round(timed_replay_us(torch, graph, K, evict), 3) for _ in range(4)]
 
-    # The kernel's average launch duration is taken from that same region: wall time
-    # between the two events / K.  Launch gaps are inside it, so it is an upper bound
-    # of the kernel's own duration (rocprofv3's per-dispatch average is the check).
-    kern_us = us_per_step
-    kern_note = ("HIP events around the K launches of the timed region / K"
-                 + (" (slab kernel + reduce kernel per step)" if spmm else ""))
-
-    # ---- region B (spmv only, reported under extras): the same K launches again,
-    # each with its own pair of events that receive that launch's begin/end time
-    # stamps.  Attaching events slows the host side, so launches are spaced out.
-    if not spmm:
-        region_us(torch, lambda i: step(i, timed=True), K)
-        durs = np.array([events.us(i) for i in range(K)])
     value = alg_bytes / us_per_step / 1e3                  # GB/s
-    achieved = alg_bytes / kern_us / 1e3
+    touched = min(K, R) * alg_bytes
+    if args.warm:
+        residency = "warm (one copy, cache resident)"
+    else:
+        residency = (f"cold: {EVICT_BYTES >> 20} MB of unrelated memory streamed right before the timed "
+                     f"region; its {K} launches read {min(K, R)} distinct copies of vals/idx "
+                     f"({touched / 1e6:.0f} MB)"
+                     + (f", a copy comes round again after {R - 1} others ({(R - 1) * alg_bytes / 1e6:.0f} MB, "
+                        f"over twice the {LLC_BYTES >> 20} MB last-level cache)" if K > R else
+                        ", each exactly once"))
+
+    traffic = None
+    rec = MEASURED_TRAFFIC.get((wl.name, "warm" if args.warm else "cold"))
+    if rec and rec["kernel"] == kernel_name:
+        traffic = rec["bytes"]
+
+    roofline = {"bound": "hbm", "achieved": round(value, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(value / HBM_PEAK_GBS, 4),
+                "traffic": traffic,
+                "kernel": kernel_name,
+                "kernel_us": round(us_per_step, 3),
+                "how": "HIP events around the K launches of the timed region / K"
+                       + (" (main kernel + reduce kernel per step)" if spmm else "")}
+
+    # ---- the machine's floor in the same protocol and the same run: an empty kernel of
+    # the product's launch shape, and a kernel that only reads the product's algorithmic
+    # bytes (rotating buffers, same eviction, same K).
+    if graph is not None and not args.warm:
+        try:
+            same = (alg_bytes + 15) // 16 * 16
+            bufs = [torch.empty(same, dtype=torch.uint8, device=dev) for _ in range(R)]
+            for b_ in bufs:
+                b_.fill_(1)
+            g_floor = capture(torch, lambda i: probe.probe_stream_read(bufs[i % R]), K, "floor: read-only kernel")
+            if g_floor is not None:
+                floor_us = min(timed_replay_us(torch, g_floor, K, evict) for _ in range(3))
+                roofline["floor_us"] = round(floor_us, 3)
+                roofline["floor_GBps"] = round(same / floor_us / 1e3, 1)
+                roofline["frac_of_floor"] = round(floor_us / us_per_step, 3)
+                roofline["floor"] = ("a kernel that only reads the same number of bytes (16 bytes per "
+                                     "lane, one piece per lane), same graph-of-K-launches protocol, "
+                                     "same eviction, rotating buffers; best of 3")
+            del bufs, g_floor
+            grid, thr = (plan.get("workgroups") or 256), (plan.get("threads") or 256)
+            g_empty = capture(torch, lambda i: probe.probe_empty(int(grid), int(thr)), max(K, 200),
+                              "floor: empty kernel")
+            if g_empty is not None:
+                roofline["empty_launch_us"] = round(
+                    min(timed_replay_us(torch, g_empty, max(K, 200)) for _ in range(3)), 3)
+            del g_empty
+        except Exception as exc:                 # never lose the headline line
+            roofline["floor_error"] = str(exc)[:200]
 
     out = {
         "metric": "bs_spmv achieved HBM GB/s" if not spmm else "bs_spmm achieved HBM GB/s",
@@ -351,23 +409,18 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: W {wl.M}x{wl.K} {wl.dtype}, bank {wl.bank}, keep {wl.k} "
                                f"({100 * wl.sparsity:.3g}% sparse), batch {wl.N}",
-                   "residency": "warm (one copy, cache resident)" if args.warm else
-                                f"cold (rotating over {R} copies, {R * alg_bytes / 1e6:.0f} MB)",
+                   "residency": residency,
+                   "bytes_touched_by_timed_launches": touched,
                    "launch": mode,
                    "algorithmic_bytes_per_step": alg_bytes,
                    "flop_per_step": wl.flops()},
-        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC.get((wl.name, "warm" if args.warm else "cold")),
-                     "kernel_us": round(kern_us, 3), "how": kern_note},
+        "roofline": roofline,
     }
 
     extras = {"gflops": round(wl.flops() / us_per_step / 1e3, 1),
               "host_wall_s_timed_region": round(t_wall, 3)}
-    if not spmm:
-        extras["per_launch_stamp_us_min_med_mean_p90"] = [
-            round(float(v), 2) for v in (durs.min(), np.median(durs), durs.mean(),
-                                         np.percentile(durs, 90))]
+    if trials:
+        extras["further_trials_us_per_step"] = trials
 
     if not args.no_extras:
         ev = HipEvents(64)
@@ -385,52 +438,33 @@ def main():
         y1 = torch.empty(1, dtype=torch.float32, device=dev)
         if not spmm:
             extras["launch_floor_us"] = round(kernel_us_of(v1, i1, Xd, y1, wl.bank), 2)
-            # the same matrix from cache (one copy): what an LSTM time step loop sees
-            w_us = kernel_us_of(vals, idx, Xd, Y, wl.bank)
-            extras["warm_kernel_us"] = round(w_us, 2)
-            extras["warm_GBps_cache_resident"] = round(alg_bytes / w_us / 1e3, 1)
-            # ... and in the protocol of `value` (a graph of launches back to back), which
-            # does not carry the time-stamp method's floor
-            gw = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(gw):
-                for _ in range(64):
-                    bs.bs_spmv(vals, idx, wl.bank, Xd, out=Y)
-            gw.replay()
-            torch.cuda.synchronize()
-            s1, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            s1.record()
-            for _ in range(10):
-                gw.replay()
-            e1.record()
-            torch.cuda.synchronize()
-            wg_us = s1.elapsed_time(e1) * 1e3 / 640
-            extras["warm_us_per_launch_graph"] = round(wg_us, 3)
-            extras["warm_GBps_per_launch_graph"] = round(alg_bytes / wg_us / 1e3, 1)
+            # the same matrix from cache (one copy): what an LSTM time step loop sees,
+            # in the protocol of `value` (a graph of launches back to back)
+            gw = capture(torch, lambda i: bs.bs_spmv(vals, idx, wl.bank, Xd, out=Y), 64, "warm product")
+            if gw is not None:
+                wg_us = min(timed_replay_us(torch, gw, 64) for _ in range(5))
+                extras["warm_us_per_launch_graph"] = round(wg_us, 3)
+                extras["warm_GBps_per_launch_graph"] = round(alg_bytes / wg_us / 1e3, 1)
             del gw
-
-        def avg_us(fn, n):
-            for _ in range(3):
-                fn(0)
-            return graph_us(torch, fn, n)
 
         # dense baseline on the unpruned-shape matrix, same residency protocol
         dense_bytes = wl.dense_bytes()
-        Rd = 1 if args.warm else max(2, -(-2 * LLC_BYTES // dense_bytes) + 1)
+        Rd = 1 if args.warm else rotation(dense_bytes)
         Wc = [Wd] + [Wd.clone() for _ in range(Rd - 1)]
         if spmm:
-            d_us = avg_us(lambda i: bs.bs_dense_gemm(Wc[i % Rd], Xd, out=Y), 20)
+            d_us = graph_us(torch, lambda i: bs.bs_dense_gemm(Wc[i % Rd], Xd, out=Y), 20, "dense gemm", evict)
         else:
-            d_us = avg_us(lambda i: bs.bs_dense_gemv(Wc[i % Rd], Xd, out=Y), 200)
+            d_us = graph_us(torch, lambda i: bs.bs_dense_gemv(Wc[i % Rd], Xd, out=Y), 200, "dense gemv", evict)
         del Wc
         extras["dense_us"] = round(d_us, 2)
         extras["dense_GBps"] = round(dense_bytes / d_us / 1e3, 1)
         extras["speedup_vs_dense"] = round(d_us / us_per_step, 2)   # both: region time per launch
         # eq. (5) of the paper with the measured dense time and the measured launch floor
-        o_time = extras.get("launch_floor_us", 0.0)
+        o_time = roofline.get("empty_launch_us", extras.get("launch_floor_us", 0.0))
         extras["ideal_us_eq5"] = round((d_us - o_time) * (1 - wl.sparsity) + o_time, 2)
         # one-time pruning + packing of the dense matrix
         p_out = (torch.empty_like(vals), torch.empty_like(idx))
-        p_us = avg_us(lambda i: bs.bs_prune_pack(Wd, wl.bank, wl.k, out=p_out), 10)
+        p_us = graph_us(torch, lambda i: bs.bs_prune_pack(Wd, wl.bank, wl.k, out=p_out), 10, "prune_pack", evict)
         p_bytes = W.nbytes + wl.nnz * (wl.val_bytes + 1)
         extras["prune_pack_us"] = round(p_us, 1)
         extras["prune_pack_GBps"] = round(p_bytes / p_us / 1e3, 1)
@@ -438,67 +472,52 @@ def main():
         if wl.k >= 2:
             k2 = wl.k // 2
             r_out = bs.bs_reprune(vals, idx, wl.bank, k2)
-            torch.cuda.synchronize()
-            gr = torch.cuda.CUDAGraph()       # a 9 us kernel: replayed from a graph, as the products are
-            with torch.cuda.graph(gr):
-                for _ in range(20):
-                    bs.bs_reprune(vals, idx, wl.bank, k2, out=r_out)
-            gr.replay()
-            torch.cuda.synchronize()
-            r_us = region_us(torch, lambda i: gr.replay(), 5) / 20
+            r_us = graph_us(torch, lambda i: bs.bs_reprune(vals, idx, wl.bank, k2, out=r_out), 20, "reprune")
             extras["reprune_to_half_us"] = round(r_us, 1)
             extras["reprune_GBps"] = round((wl.nnz + wl.M * (wl.K // wl.bank) * k2) *
                                            (wl.val_bytes + 1) / r_us / 1e3, 1)
         ev.close()
 
-        # the machine's floor, measured with the library's helper kernels in the same
-        # protocol (a graph of launches): an empty launch, a kernel that only reads this
-        # workload's bytes (cold, rotating buffers), and a large streaming read
+        # more of the machine's floor: a large streaming read, LDS gather rates, and the
+        # grid-wide barrier a persistent multi-step kernel would need once per step
         try:
-            def floor_graph_us(launch, n):
-                side2 = torch.cuda.Stream()
-                with torch.cuda.stream(side2):
-                    for i in range(min(n, 8)):
-                        launch(i)
-                torch.cuda.synchronize()
-                gp = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(gp):
-                    for i in range(n):
-                        launch(i)
-                gp.replay()
-                torch.cuda.synchronize()
-                return region_us(torch, lambda i: gp.replay(), 3) / n
-
             floor = {}
-            floor["empty_launch_us"] = round(floor_graph_us(lambda i: bs.bs_probe_empty(750, 256), 1000), 3)
-            same = (alg_bytes + 15) // 16 * 16
-            n_same = max(2, -(-2 * LLC_BYTES // same) + 1)
-            bufs = [torch.empty(same, dtype=torch.uint8, device=dev) for _ in range(n_same)]
-            for b_ in bufs:
-                b_.fill_(1)
-            t_same = floor_graph_us(lambda i: bs.bs_probe_stream_read(bufs[i % n_same]), 2 * n_same)
-            floor["stream_read_same_bytes_us"] = round(t_same, 3)
-            floor["stream_read_same_bytes_GBps"] = round(same / t_same / 1e3, 1)
-            del bufs
             big = 288 << 20
             bufs = [torch.empty(big, dtype=torch.uint8, device=dev) for _ in range(3)]
             for b_ in bufs:
                 b_.fill_(1)
-            t_big = floor_graph_us(lambda i: bs.bs_probe_stream_read(bufs[i % 3]), 12)
+            t_big = graph_us(torch, lambda i: probe.probe_stream_read(bufs[i % 3]), 12, "floor: 288 MB read")
             floor["stream_read_288MB_us"] = round(t_big, 2)
             floor["stream_read_288MB_GBps"] = round(big / t_big / 1e3, 1)
-            floor["value_over_same_bytes_stream"] = round(t_same / us_per_step, 3)
             del bufs
-            # what an LDS gather costs (the SpMM kernels' inner loop): 256 workgroups of 768
-            # lanes that only issue 16-byte LDS reads; ns per wavefront read and compute unit
+            # what an LDS gather costs: 256 workgroups of 768 lanes that only issue LDS reads;
+            # ns per wavefront read and compute unit
             reads, thr = 16000, 768
-            t0 = floor_graph_us(lambda i: bs.bs_probe_lds_gather(thr, 0, 16, 8), 4)   # fill + launch only
+            t0 = graph_us(torch, lambda i: probe.probe_lds_gather(thr, 0, 16, 8), 4, "floor: lds fill")
             lds = {}
-            for key, pattern, lanes in (("adjacent_1KB", 0, 16), ("rows_of_256B", 1, 16),
-                                        ("rows_of_128B", 1, 8), ("rows_of_64B", 1, 4), ("rows_of_32B", 1, 2)):
-                t = floor_graph_us(lambda i: bs.bs_probe_lds_gather(thr, pattern, lanes, reads), 4)
+            for key, pattern, lanes in (("b128_adjacent_1KB", 0, 16), ("b128_rows_of_256B", 1, 16),
+                                        ("b128_rows_of_128B", 1, 8), ("b128_rows_of_64B", 1, 4),
+                                        ("b128_rows_of_32B", 1, 2), ("b32_random_word_per_lane", 2, 16),
+                                        ("b32_random_row_word_is_lane", 3, 16)):
+                t = graph_us(torch, lambda i: probe.probe_lds_gather(thr, pattern, lanes, reads), 4,
+                             "floor: lds gather")
                 lds[key] = round((t - t0) * 1e3 / ((reads - 8) * thr / 64), 3)
             floor["lds_gather_ns_per_wavefront_read_per_cu"] = lds
+            # grid barrier: workgroups -> us per round (256 lanes each, a 6 KB vector read and
+            # rewritten per round as an LSTM-1500 step would; bounded waits)
+            sync = torch.zeros(4, dtype=torch.int32, device=dev)
+            hbuf = torch.zeros(2 * 1500, dtype=torch.float32, device=dev)
+            bar = {}
+            n_rounds = 500
+            for wgs in (32, 64, 128, 256):
+                for bmode, tag in ((0, "acquire_polls"), (1, "relaxed_polls")):
+                    sync.zero_()
+                    us = region_us(torch, lambda i: probe.probe_grid_barrier(wgs, 256, n_rounds, 1500, bmode,
+                                                                             sync, hbuf), 1) / n_rounds
+                    arrivals, aborted = (int(v) for v in sync[:2].tolist())
+                    bar[f"{wgs}_wgs_{tag}"] = {"us_per_round": round(us, 2),
+                                               "complete": arrivals == n_rounds * wgs and not aborted}
+            floor["grid_barrier"] = bar
             extras["machine_floor"] = floor
         except Exception as exc:                 # never lose the headline line
             extras["machine_floor_error"] = str(exc)[:200]
@@ -513,25 +532,13 @@ def main():
                 Xs_h, h0_h, c0_h, b_h = workloads.draw_lstm_inputs(Hn, In, T, wl.seed)
                 Xs, h0, c0, bias = (torch.from_numpy(t).to(dev) for t in (Xs_h, h0_h, c0_h, b_h))
                 H_all = torch.empty((T, Hn), dtype=torch.float32, device=dev)
-                side = torch.cuda.Stream()
-                with torch.cuda.stream(side):
-                    bs.bs_lstm_sequence(vals, idx, wl.bank, Xs, h0, bias, c0, H_all=H_all)
-                torch.cuda.synchronize()
-                gl = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(gl):
-                    bs.bs_lstm_sequence(vals, idx, wl.bank, Xs, h0, bias, c0, H_all=H_all)
-                gl.replay()
-                torch.cuda.synchronize()
-                s2, e2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                s2.record()
-                for _ in range(10):
-                    gl.replay()
-                e2.record()
-                torch.cuda.synchronize()
-                l_us = s2.elapsed_time(e2) * 1e3 / (10 * T)
-                extras["lstm_step_us_cache_resident"] = round(l_us, 3)
-                extras["lstm_steps_per_graph"] = T
-                extras["lstm_step_vs_dense_gemv_us"] = round(d_us, 2)
+                gl = capture(torch, lambda i: bs.bs_lstm_sequence(vals, idx, wl.bank, Xs, h0, bias, c0,
+                                                                  H_all=H_all), 1, "lstm sequence")
+                if gl is not None:
+                    l_us = min(timed_replay_us(torch, gl, T) for _ in range(5))
+                    extras["lstm_step_us_cache_resident"] = round(l_us, 3)
+                    extras["lstm_steps_per_graph"] = T
+                    extras["lstm_step_vs_dense_gemv_us"] = round(d_us, 2)
             except Exception as exc:             # never lose the headline line
                 extras["lstm_error"] = str(exc)[:200]
 
@@ -550,14 +557,19 @@ def main():
         # fewer launches: {us per launch, GB/s of algorithmic bytes, dense baseline us}
         if not args.warm and args.workload == "lstm1500":
             del copies, calls
+            only = [n for n in args.only.split(",") if n]
             others = {}
-            for name in OTHER_WORKLOADS:
+            for name in (only or OTHER_WORKLOADS):
+                if name not in workloads.WORKLOADS:
+                    continue
                 try:
-                    others[name] = quick_measure(torch, np, bs, workloads, dev, name, o_time)
+                    others[name] = quick_measure(torch, np, bs, workloads, dev, name, o_time, evict)
                 except Exception as exc:             # never lose the headline line
                     others[name] = {"error": str(exc)[:200]}
                 torch.cuda.empty_cache()
             extras["other_workloads_cold"] = others
+    if EAGER_FALLBACKS:
+        extras["timed_as_eager_launches"] = EAGER_FALLBACKS
     out["extras"] = extras
 
     if not args.no_cpu:
@@ -580,8 +592,6 @@ def main():
                                "sample": f"{n_calls} full products of the same workload "
                                          f"in {el:.1f} s (fp64 accumulate, rows split over threads)",
                                "us_per_call": round(el / n_calls * 1e6, 1)}
-    if events:
-        events.close()
     print(json.dumps(out))
     return 0
 

@@ -20,6 +20,12 @@
  *   - Pointers marked DEVICE are device pointers owned by the caller; the
  *     library neither allocates nor frees nor keeps them.  A `workspace` is
  *     caller-owned device memory too.
+ *   - State: the only thing the library remembers between calls is, per kernel and
+ *     device, that the kernel's LDS limit has been raised (an atomic bit mask; calls
+ *     are safe from several threads).  That step happens at a kernel's first launch
+ *     on a device, or for all kernels at once in bs_init(), and never while the
+ *     stream is being captured: a first use inside a capture returns
+ *     BS_ERR_NOT_INITIALISED and enqueues nothing.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *     Calls only enqueue work on it; they never synchronise.
  *   - Outputs are fully overwritten; they need no initialisation.
@@ -47,11 +53,23 @@ typedef enum {
     BS_ERR_UNSUPPORTED = 3, /* bank > 256, unknown dtype, size over a stated limit */
     BS_ERR_ALIGN = 4,       /* a base pointer is not 16-byte aligned              */
     BS_ERR_HIP = 5,         /* the HIP runtime refused the launch                 */
-    BS_ERR_WORKSPACE = 6    /* workspace missing or smaller than required         */
+    BS_ERR_WORKSPACE = 6,   /* workspace missing or smaller than required         */
+    BS_ERR_NOT_INITIALISED = 7 /* first use of a kernel inside a stream capture     */
 } bs_status;
 
 /* storage type of W and vals; x, X, y, Y and all accumulation are fp32 */
 typedef enum { BS_F32 = 0, BS_F16 = 1 } bs_dtype;
+
+/* ---- set-up ---------------------------------------------------------------- */
+
+/*
+ * Optional.  Prepares every kernel of the library on the CURRENT device (raises the
+ * LDS limit of those that use more than 48 KB), so that no later call has to.  Call
+ * it once per device before capturing a stream whose first-ever library calls would
+ * otherwise happen inside the capture.  Not a stream operation; safe to call from
+ * several threads and more than once.
+ */
+int bs_init(void);
 
 /* ---- sizes (host only, no GPU needed) ----------------------------------- */
 
@@ -123,6 +141,21 @@ int bs_spmv_ex(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64
                int bank, int k, const float* x, float* y,
                int lanes_per_row, int rows_per_wg,
                void* start_event, void* stop_event, void* stream);
+
+/*
+ * The launch bs_spmv_ex would make for this shape and these overrides (host only, no GPU
+ * call), for tests, tuning sweeps and for naming the kernel a measurement belongs to.
+ * Writes up to n_out of these 10 values to out (HOST):
+ *   [0] 1 if x is walked in slabs (K > 40960; the remaining values are then 0)
+ *   [1] entries per 16-byte chunk   [2] lanes per row   [3] chunk slots per lane
+ *   [4] threads per workgroup       [5] rows per workgroup   [6] workgroups
+ *   [7] LDS bytes per workgroup     [8] 1 if the per-entry bank table is used
+ *   [9] how banks are found without the table (0: a chunk stays in its bank, 1: at most two
+ *       banks per chunk, 2: any)
+ * Returns BS_OK, or the status bs_spmv_ex would return.
+ */
+int bs_spmv_plan(int dtype, int64_t M, int64_t K, int bank, int k, int lanes_per_row,
+                 int rows_per_wg, int64_t* out, int n_out);
 
 /* ---- Y = W_sparse . X  (Sec. 3.4 / Sec. 4.1, batch size > 1; im2col conv) - */
 
@@ -201,33 +234,6 @@ int bs_dense_gemv(const void* W, int dtype, int64_t M, int64_t K,
 /* Y = W . X;  X K x N (ldx), Y M x N (ldy), fp32 */
 int bs_dense_gemm(const void* W, int dtype, int64_t M, int64_t K,
                   const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy, void* stream);
-
-/* ---- measurement helpers (not part of the method) --------------------------
- *
- * For benchmarks that must tell a kernel's quality from the machine's floor (the
- * products of Sec. 4 last a few microseconds on this GPU):
- * bs_probe_empty        launches an empty kernel of `grid` workgroups of `threads`
- *                       lanes (1..1024, a multiple of 64);
- * bs_probe_stream_read  a kernel that only reads `bytes` bytes (a multiple of 16,
- *                       at least 16) from DEVICE `src`, 16 bytes per lane and load, and
- *                       stores nothing; `sink` is DEVICE memory of at least 256 bytes
- *                       that is never written for real data (may be NULL).
- * bs_probe_lds_gather   256 workgroups of `threads` lanes (64..1024, a multiple of 64) fill
- *                       120 KB of LDS and then issue `reads` (a multiple of 8) 16-byte LDS
- *                       reads per lane and nothing else: the gather rate the SpMM kernels
- *                       live on.  pattern 0: a wavefront reads 1 KB of adjacent bytes;
- *                       pattern 1: groups of `group_lanes` (2, 4, 8 or 16) neighbouring lanes
- *                       read adjacent 16-byte pieces of one row of group_lanes*16 bytes,
- *                       every group a random row (the rows of X that the entries of
- *                       different matrix rows point at).  `sink` as above.
- *                       Time per wavefront read and compute unit = kernel time /
- *                       (reads * threads / 64).
- * All enqueue on `stream` like every other call.
- */
-int bs_probe_empty(int grid, int threads, void* stream);
-int bs_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream);
-int bs_probe_lds_gather(int threads, int pattern, int group_lanes, int reads, void* sink,
-                        void* stream);
 
 #ifdef __cplusplus
 }

@@ -19,10 +19,9 @@ _LIB_PATH = os.path.join(_HERE, "libbs.so")
 BS_F32, BS_F16 = 0, 1
 
 EXPORTS = (
-    "bs_nnz", "bs_vals_bytes", "bs_idx_bytes", "bs_status_str", "bs_prune_pack", "bs_spmv",
-    "bs_spmv_ex", "bs_spmm_workspace_bytes", "bs_spmm_plan", "bs_spmm", "bs_dense_gemv", "bs_dense_gemm",
-    "bs_lstm_step", "bs_lstm_sequence", "bs_reprune", "bs_probe_empty", "bs_probe_stream_read",
-    "bs_probe_lds_gather",
+    "bs_init", "bs_nnz", "bs_vals_bytes", "bs_idx_bytes", "bs_status_str", "bs_prune_pack", "bs_spmv",
+    "bs_spmv_ex", "bs_spmv_plan", "bs_spmm_workspace_bytes", "bs_spmm_plan", "bs_spmm", "bs_dense_gemv", "bs_dense_gemm",
+    "bs_lstm_step", "bs_lstm_sequence", "bs_reprune",
 )
 
 
@@ -61,6 +60,8 @@ def load_library():
     lib.bs_prune_pack.argtypes = [vp, i32, i64, i64, i32, i32, vp, vp, vp]
     lib.bs_spmv.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, vp, vp]
     lib.bs_spmv_ex.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, vp, i32, i32, vp, vp, vp]
+    lib.bs_spmv_plan.argtypes = [i32, i64, i64, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_int64), i32]
+    lib.bs_spmv_plan.restype = i32
     lib.bs_spmm_workspace_bytes.argtypes = [i32, i64, i64, i32, i32, i64]
     lib.bs_spmm_workspace_bytes.restype = sz
     lib.bs_spmm_plan.argtypes = [i32, i64, i64, i32, i32, i64, ctypes.POINTER(ctypes.c_int64), i32]
@@ -68,15 +69,12 @@ def load_library():
     lib.bs_spmm.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, i64, vp, i64, vp, sz, vp]
     lib.bs_dense_gemv.argtypes = [vp, i32, i64, i64, vp, vp, vp]
     lib.bs_dense_gemm.argtypes = [vp, i32, i64, i64, vp, i64, i64, vp, i64, vp]
-    lib.bs_probe_empty.argtypes = [i32, i32, vp]
-    lib.bs_probe_stream_read.argtypes = [vp, sz, vp, vp]
-    lib.bs_probe_lds_gather.argtypes = [i32, i32, i32, i32, vp, vp]
     lib.bs_reprune.argtypes = [vp, vp, i32, i64, i64, i32, i32, i32, vp, vp, vp]
     lib.bs_lstm_step.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.bs_lstm_sequence.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, vp, vp, vp, vp, vp]
-    for name in ("bs_prune_pack", "bs_spmv", "bs_spmv_ex", "bs_spmm", "bs_dense_gemv",
-                 "bs_dense_gemm", "bs_lstm_step", "bs_lstm_sequence", "bs_reprune", "bs_probe_empty",
-                 "bs_probe_stream_read", "bs_probe_lds_gather"):
+    lib.bs_init.argtypes = []
+    for name in ("bs_init", "bs_prune_pack", "bs_spmv", "bs_spmv_ex", "bs_spmm", "bs_dense_gemv",
+                 "bs_dense_gemm", "bs_lstm_step", "bs_lstm_sequence", "bs_reprune"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -130,6 +128,12 @@ def _check(status: int, call: str):
         raise BsError(status, call)
 
 
+def bs_init():
+    """Prepare every kernel on the current device (optional; needed only before a capture
+    whose first-ever library calls would happen inside it)."""
+    _check(load_library().bs_init(), "bs_init")
+
+
 # ------------------------------------------------------------ host-only calls
 
 def bs_nnz(M: int, K: int, bank: int, k: int) -> int:
@@ -150,6 +154,19 @@ def bs_status_str(status: int) -> str:
 
 def bs_spmm_workspace_bytes(dtype: int, M: int, K: int, bank: int, k: int, N: int) -> int:
     return load_library().bs_spmm_workspace_bytes(dtype, M, K, bank, k, N)
+
+
+SPMV_PLAN_FIELDS = ("slab_kernel", "ch", "lpr", "u", "threads", "rows_per_wg", "workgroups", "lds_bytes",
+                    "table", "bank_mode")
+
+
+def bs_spmv_plan(dtype: int, M: int, K: int, bank: int, k: int, lanes_per_row: int = 0,
+                 rows_per_wg: int = 0) -> dict:
+    """The launch bs_spmv / bs_spmv_ex would make (host only).  Raises on an unsupported shape."""
+    out = (ctypes.c_int64 * len(SPMV_PLAN_FIELDS))()
+    _check(load_library().bs_spmv_plan(dtype, M, K, bank, k, lanes_per_row, rows_per_wg, out,
+                                       len(SPMV_PLAN_FIELDS)), "bs_spmv_plan")
+    return dict(zip(SPMV_PLAN_FIELDS, (int(v) for v in out)))
 
 
 SPMM_PLAN_FIELDS = ("rows_kernel", "ch", "nl", "nt", "n_tiles", "sb", "n_slabs", "lpr", "u", "threads",
@@ -374,23 +391,3 @@ def bs_reprune(vals, idx, bank: int, k2: int, out=None):
     _check(load_library().bs_reprune(_ptr(vals), _ptr(idx), code, M, K, bank, k, k2, _ptr(vals2),
                                      _ptr(idx2), _stream()), "bs_reprune")
     return vals2, idx2
-
-
-def bs_probe_empty(grid: int = 256, threads: int = 256):
-    """Measurement helper: launch an empty kernel on the current stream."""
-    _check(load_library().bs_probe_empty(grid, threads, _stream()), "bs_probe_empty")
-
-
-def bs_probe_stream_read(src: torch.Tensor, sink: torch.Tensor = None):
-    """Measurement helper: a kernel that only reads all of `src` (bytes a multiple of 16)."""
-    _dev(src, "src")
-    nbytes = src.numel() * src.element_size()
-    _check(load_library().bs_probe_stream_read(_ptr(src), nbytes, _ptr(sink), _stream()),
-           "bs_probe_stream_read")
-
-
-def bs_probe_lds_gather(threads: int = 768, pattern: int = 1, group_lanes: int = 8, reads: int = 16000):
-    """Measurement helper: 256 workgroups that only issue 16-byte LDS reads (`reads` per lane);
-    pattern 0 = adjacent bytes, 1 = groups of `group_lanes` lanes on random rows."""
-    _check(load_library().bs_probe_lds_gather(threads, pattern, group_lanes, reads, None, _stream()),
-           "bs_probe_lds_gather")

@@ -1,6 +1,47 @@
 // C-ABI entry points of libbs.so: argument validation on the host, then the
-// launchers.  Nothing here allocates, synchronises or keeps state.
+// launchers.  Nothing here allocates or synchronises.  The only state the library keeps
+// is which kernels have had their LDS limit raised on which device (below).
 #include "bs_internal.h"
+
+namespace bs {
+
+LdsKernel* g_lds_kernels = nullptr;
+
+LdsKernel::LdsKernel(const void* f) : fn(f), raised(0), next(g_lds_kernels) { g_lds_kernels = this; }
+
+namespace {
+int raise_on_current_device(LdsKernel& k, uint64_t bit) {
+    if (hipFuncSetAttribute(k.fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes) != hipSuccess)
+        return BS_ERR_HIP;
+    k.raised.fetch_or(bit, std::memory_order_release);
+    return BS_OK;
+}
+}  // namespace
+
+int ensure_lds_limit(LdsKernel& k, hipStream_t st) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) return BS_ERR_HIP;
+    const uint64_t bit = (uint64_t)1 << dev;
+    if (k.raised.load(std::memory_order_acquire) & bit) return BS_OK;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess) return BS_ERR_HIP;
+    if (cs != hipStreamCaptureStatusNone) return BS_ERR_NOT_INITIALISED;
+    return raise_on_current_device(k, bit);
+}
+
+int init_current_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) return BS_ERR_HIP;
+    const uint64_t bit = (uint64_t)1 << dev;
+    for (LdsKernel* k = g_lds_kernels; k; k = k->next) {
+        if (k->raised.load(std::memory_order_acquire) & bit) continue;
+        const int st = raise_on_current_device(*k, bit);
+        if (st != BS_OK) return st;
+    }
+    return BS_OK;
+}
+
+}  // namespace bs
 
 namespace {
 
@@ -30,6 +71,8 @@ int check_packed(const void* vals, const uint8_t* idx, int dtype, int64_t M, int
 
 extern "C" {
 
+int bs_init(void) { return bs::init_current_device(); }
+
 size_t bs_nnz(int64_t M, int64_t K, int bank, int k) {
     if (!shape_ok(M, K, bank, k) || !size_ok(M, K, bank)) return 0;
     return (size_t)M * (size_t)(K / bank) * (size_t)k;
@@ -42,34 +85,6 @@ size_t bs_vals_bytes(int64_t M, int64_t K, int bank, int k, int dtype) {
 
 size_t bs_idx_bytes(int64_t M, int64_t K, int bank, int k) { return bs_nnz(M, K, bank, k); }
 
-int bs_probe_empty(int grid, int threads, void* stream) {
-    if (grid < 1 || grid > 65536 || threads < 64 || threads > 1024 || threads % 64)
-        return BS_ERR_SHAPE;
-    return bs::launch_probe_empty(grid, threads, static_cast<hipStream_t>(stream));
-}
-
-int bs_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
-    if (!src) return BS_ERR_NULL;
-    if (bytes < 16 || bytes % 16) return BS_ERR_SHAPE;
-    if (!aligned16(src) || (sink && !aligned16(sink))) return BS_ERR_ALIGN;
-    return bs::launch_probe_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream));
-}
-
-int bs_probe_lds_gather(int threads, int pattern, int group_lanes, int reads, void* sink,
-                        void* stream) {
-    if (threads < 64 || threads > 1024 || threads % 64 || reads < 8 || reads % 8) return BS_ERR_SHAPE;
-    if (pattern != 0 && pattern != 1) return BS_ERR_SHAPE;
-    int shift = 4;
-    if (pattern == 1) {
-        if (group_lanes != 2 && group_lanes != 4 && group_lanes != 8 && group_lanes != 16)
-            return BS_ERR_SHAPE;
-        shift = group_lanes == 2 ? 1 : group_lanes == 4 ? 2 : group_lanes == 8 ? 3 : 4;
-    }
-    if (sink && !aligned16(sink)) return BS_ERR_ALIGN;
-    return bs::launch_probe_lds_gather(threads, pattern, shift, reads, sink,
-                                       static_cast<hipStream_t>(stream));
-}
-
 const char* bs_status_str(int status) {
     switch (status) {
         case BS_OK: return "ok";
@@ -79,6 +94,8 @@ const char* bs_status_str(int status) {
         case BS_ERR_ALIGN: return "pointer not 16-byte aligned";
         case BS_ERR_HIP: return "HIP runtime error";
         case BS_ERR_WORKSPACE: return "workspace missing or too small";
+        case BS_ERR_NOT_INITIALISED:
+            return "first use of a kernel inside a stream capture: call bs_init() on this device first";
     }
     return "unknown status";
 }
@@ -117,6 +134,15 @@ int bs_spmv_ex(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64
                            static_cast<hipEvent_t>(start_event),
                            static_cast<hipEvent_t>(stop_event),
                            static_cast<hipStream_t>(stream));
+}
+
+int bs_spmv_plan(int dtype, int64_t M, int64_t K, int bank, int k, int lanes_per_row, int rows_per_wg,
+                 int64_t* out, int n_out) {
+    if (!out) return BS_ERR_NULL;
+    if (!shape_ok(M, K, bank, k) || n_out < 0) return BS_ERR_SHAPE;
+    if (!dtype_ok(dtype) || !size_ok(M, K, bank) || lanes_per_row < 0 || rows_per_wg < 0)
+        return BS_ERR_UNSUPPORTED;
+    return bs::spmv_plan_describe(dtype, M, K, bank, k, lanes_per_row, rows_per_wg, out, n_out);
 }
 
 int bs_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,

@@ -182,16 +182,10 @@ int gemm_stream_launch(const VT* w, int64_t M, int64_t K, const float* X, int64_
     const int rows_per_wg = threads / kWave * R;
     const int64_t grid = (M + rows_per_wg - 1) / rows_per_wg;
     const size_t lds = (size_t)(KS + 4) * NC * sizeof(float);
-    auto kern = dense_gemm_stream<VT, NC, R, P>;
+    constexpr auto kern = dense_gemm_stream<VT, NC, R, P>;
     if (lds > 48 * 1024) {
-        static bool raised = false;
-        if (!raised) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kMaxLdsBytes) != hipSuccess)
-                return BS_ERR_HIP;
-            raised = true;
-        }
+        const int st_code = ensure_lds_limit(LdsKernelOf<kern>::reg, st);
+        if (st_code != BS_OK) return st_code;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(threads), lds, st, w, X, Y, (int)M, (int)K,
                        (int)N, ldx, ldy);

@@ -8,6 +8,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/bs.h"
 
 namespace bs {
@@ -23,6 +25,8 @@ int launch_reprune(const void* vals, const uint8_t* idx, int dtype, int64_t n_ba
 int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
                 int k, const float* x, float* y, int lanes_per_row, int rows_per_wg,
                 hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st);
+int spmv_plan_describe(int dtype, int64_t M, int64_t K, int bank, int k, int lanes_per_row,
+                       int rows_per_wg, int64_t* out, int n_out);
 // the same product for x larger than one compute unit's LDS (bs_spmv_slab.hip)
 int launch_spmv_slabbed(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K,
                         int bank, int k, const float* x, float* y, hipEvent_t ev_start,
@@ -41,13 +45,35 @@ int launch_dense_gemv(const void* W, int dtype, int64_t M, int64_t K, const floa
                       hipStream_t st);
 int launch_dense_gemm(const void* W, int dtype, int64_t M, int64_t K, const float* X, int64_t N,
                       int64_t ldx, float* Y, int64_t ldy, hipStream_t st);
-// measurement helpers (bs_probe.hip)
-int launch_probe_empty(int grid, int threads, hipStream_t st);
-int launch_probe_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st);
-int launch_probe_lds_gather(int threads, int pattern, int group_shift, int reads, void* sink,
-                            hipStream_t st);
-
 inline int hip_status(hipError_t e) { return e == hipSuccess ? BS_OK : BS_ERR_HIP; }
+
+// ---- kernels that may use more than 48 KB of LDS --------------------------------
+// Such a kernel needs its dynamic-LDS limit raised once per device.  Every one of them
+// owns an LdsKernel that links itself into one list when the library is loaded, so that
+// bs_init() can raise them all; a launcher calls ensure_lds_limit() before launching.
+// `raised` has one bit per device number; raising a limit twice is harmless, so two
+// threads that race here both succeed.
+struct LdsKernel {
+    const void* fn;
+    std::atomic<uint64_t> raised;
+    LdsKernel* next;
+    explicit LdsKernel(const void* f);
+};
+extern LdsKernel* g_lds_kernels;   // bs_api.hip; constant-initialised, filled at load time
+
+template <auto KERNEL>
+struct LdsKernelOf {
+    static LdsKernel reg;
+};
+template <auto KERNEL>
+LdsKernel LdsKernelOf<KERNEL>::reg{reinterpret_cast<const void*>(KERNEL)};
+
+// BS_OK when the kernel's limit is raised on the current device.  The limit is never
+// changed while `st` is being captured: BS_ERR_NOT_INITIALISED then (call bs_init() on
+// this device first, or make the first call outside the capture).
+int ensure_lds_limit(LdsKernel& k, hipStream_t st);
+// raises every registered kernel's limit on the current device (bs_init)
+int init_current_device();
 
 // Multiplier m with floor(e / d) == __umulhi(e, m) for every e with e * d < 2^32
 // (d >= 2).  d == 1 is handled by the caller (quotient = e).

@@ -329,16 +329,10 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
 
 template <typename VT, int CH, int LPR, int U, int Q>
 int spmm_launch_one(const SpmmArgs& a, const SpmmLaunch& l) {
-    auto kern = spmm_kernel<VT, CH, LPR, U, Q>;
+    constexpr auto kern = spmm_kernel<VT, CH, LPR, U, Q>;
     if (l.lds > 48 * 1024) {
-        static bool raised = false;   // per instantiation; raising it twice is harmless
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               kMaxLdsBytes);
-            if (e != hipSuccess) return BS_ERR_HIP;
-            raised = true;
-        }
+        const int st_code = ensure_lds_limit(LdsKernelOf<kern>::reg, l.st);
+        if (st_code != BS_OK) return st_code;
     }
     hipLaunchKernelGGL(kern, dim3(a.wgs_per_xcd * kXcds), dim3(l.threads), l.lds, l.st, a);
     return hip_status(hipGetLastError());

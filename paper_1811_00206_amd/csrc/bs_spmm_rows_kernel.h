@@ -257,16 +257,10 @@ __global__ __launch_bounds__(1024) void spmm_rows_kernel(SpmmArgs a) {
 
 template <typename VT, int CH>
 int spmm_rows_launch_one(const SpmmArgs& a, const SpmmLaunch& l) {
-    auto kern = spmm_rows_kernel<VT, CH, 4>;
+    constexpr auto kern = spmm_rows_kernel<VT, CH, 4>;
     if (l.lds > 48 * 1024) {
-        static bool raised = false;   // per instantiation; raising it twice is harmless
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               kMaxLdsBytes);
-            if (e != hipSuccess) return BS_ERR_HIP;
-            raised = true;
-        }
+        const int st_code = ensure_lds_limit(LdsKernelOf<kern>::reg, l.st);
+        if (st_code != BS_OK) return st_code;
     }
     hipLaunchKernelGGL(kern, dim3(a.wgs_per_xcd * kXcds), dim3(l.threads), l.lds, l.st, a);
     return hip_status(hipGetLastError());

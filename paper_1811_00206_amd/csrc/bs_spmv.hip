@@ -14,11 +14,19 @@ struct LstmPart {
     int H, I;
 };
 
-// Shared by bs_spmv and the fused LSTM step (lstm != nullptr: M = 4H, K = I + H,
-// x is the first I entries of the input vector, y is unused).
-int launch_common(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
-                  int k, const float* x, float* y, int lanes_per_row, int rows_per_wg,
-                  const LstmPart* lstm, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st) {
+// The launch shape for one product.  lstm: the fused step (M = 4H, K = I + H).
+struct SpmvPlan {
+    bool slab;              // x does not fit LDS: bs_spmv_slab.hip, nothing else below is set
+    int ch, lpr, u, rpw, threads;
+    int64_t grid;
+    size_t lds;
+    int table_off, bank_mode, pre_off;
+    int64_t row_len, cpr;
+};
+
+int plan_spmv(int dtype, int64_t M, int64_t K, int bank, int k, int lanes_per_row, int rows_per_wg,
+              bool lstm, SpmvPlan& p) {
+    p = SpmvPlan{};
     const int64_t row_len = (K / bank) * k;
     // LDS: x, then (if it fits) one word per row entry for the bank table
     const size_t x_floats = ((size_t)K + 3) / 4 * 4;
@@ -28,7 +36,8 @@ int launch_common(const void* vals, const uint8_t* idx, int dtype, int64_t M, in
         // x does not fit one compute unit's LDS: the slab-by-slab kernel (no launch-shape
         // overrides, no fused LSTM step there)
         if (lstm || lanes_per_row != 0 || rows_per_wg != 0) return BS_ERR_UNSUPPORTED;
-        return launch_spmv_slabbed(vals, idx, dtype, M, K, bank, k, x, y, ev_start, ev_stop, st);
+        p.slab = true;
+        return BS_OK;
     }
     int table_off = 0;
     if (lds + (size_t)row_len * 4 <= (size_t)kMaxLdsBytes) {
@@ -77,26 +86,42 @@ int launch_common(const void* vals, const uint8_t* idx, int dtype, int64_t M, in
     }
     const int64_t grid = (M + rpw - 1) / rpw;
     if (grid > INT32_MAX) return BS_ERR_UNSUPPORTED;
+    p.ch = ch; p.lpr = lpr; p.u = u; p.rpw = rpw; p.threads = (int)threads; p.grid = grid;
+    p.lds = lds; p.table_off = table_off; p.pre_off = pre_off;
+    p.bank_mode = (k % ch == 0) ? 0 : (k >= ch ? 1 : 2);
+    p.row_len = row_len; p.cpr = cpr;
+    return BS_OK;
+}
+
+// Shared by bs_spmv and the fused LSTM step (lstm != nullptr: M = 4H, K = I + H,
+// x is the first I entries of the input vector, y is unused).
+int launch_common(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                  int k, const float* x, float* y, int lanes_per_row, int rows_per_wg,
+                  const LstmPart* lstm, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st) {
+    SpmvPlan p;
+    const int rc = plan_spmv(dtype, M, K, bank, k, lanes_per_row, rows_per_wg, lstm != nullptr, p);
+    if (rc != BS_OK) return rc;
+    if (p.slab) return launch_spmv_slabbed(vals, idx, dtype, M, K, bank, k, x, y, ev_start, ev_stop, st);
 
     SpmvArgs a;
     a.vals = vals; a.idx = idx; a.x = x; a.y = y;
     a.M = (int)M; a.K = (int)K; a.B = bank; a.k = k;
     a.magic_k = magic_u32((uint32_t)k);
-    a.row_len = (int)row_len;
-    a.chunks_per_row = (int)cpr;
-    a.rows_per_wg = rpw;
-    a.bank_mode = (k % ch == 0) ? 0 : (k >= ch ? 1 : 2);
-    a.table_off = table_off;
+    a.row_len = (int)p.row_len;
+    a.chunks_per_row = (int)p.cpr;
+    a.rows_per_wg = p.rpw;
+    a.bank_mode = p.bank_mode;
+    a.table_off = p.table_off;
     a.h_in = nullptr; a.bias = nullptr; a.c_in = nullptr; a.c_out = nullptr; a.h_out = nullptr;
-    a.H = 0; a.I = 0; a.pre_off = pre_off;
+    a.H = 0; a.I = 0; a.pre_off = p.pre_off;
     if (lstm) {
         a.h_in = lstm->h_in; a.bias = lstm->bias; a.c_in = lstm->c_in;
         a.c_out = lstm->c_out; a.h_out = lstm->h_out; a.H = lstm->H; a.I = lstm->I;
     }
 
-    const SpmvLaunch l{lstm != nullptr, (int)threads, (int)grid, lds, ev_start, ev_stop, st};
-    if (dtype == BS_F16) return spmv_launch_f16(ch, lpr, u, a, l);
-    return spmv_launch_f32(ch, lpr, u, a, l);
+    const SpmvLaunch l{lstm != nullptr, p.threads, (int)p.grid, p.lds, ev_start, ev_stop, st};
+    if (dtype == BS_F16) return spmv_launch_f16(p.ch, p.lpr, p.u, a, l);
+    return spmv_launch_f32(p.ch, p.lpr, p.u, a, l);
 }
 
 }  // namespace
@@ -106,6 +131,17 @@ int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int6
                 hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t st) {
     return launch_common(vals, idx, dtype, M, K, bank, k, x, y, lanes_per_row, rows_per_wg,
                          nullptr, ev_start, ev_stop, st);
+}
+
+int spmv_plan_describe(int dtype, int64_t M, int64_t K, int bank, int k, int lanes_per_row,
+                       int rows_per_wg, int64_t* out, int n_out) {
+    SpmvPlan p;
+    const int rc = plan_spmv(dtype, M, K, bank, k, lanes_per_row, rows_per_wg, false, p);
+    if (rc != BS_OK) return rc;
+    const int64_t v[10] = {p.slab ? 1 : 0, p.ch, p.lpr, p.u, p.threads, p.rpw, p.grid, (int64_t)p.lds,
+                           p.table_off > 0 ? 1 : 0, p.bank_mode};
+    for (int i = 0; i < n_out && i < 10; ++i) out[i] = v[i];
+    return BS_OK;
 }
 
 int launch_lstm_step(const void* vals, const uint8_t* idx, int dtype, int64_t H, int64_t I, int bank,

@@ -350,16 +350,10 @@ __global__ __launch_bounds__(1024) void spmv_kernel(SpmvArgs a) {
 
 template <typename VT, int CH, int LPR, int U, bool LSTM = false>
 int spmv_launch_one(const SpmvArgs& a, const SpmvLaunch& l) {
-    auto kern = spmv_kernel<VT, CH, LPR, U, LSTM>;
+    constexpr auto kern = spmv_kernel<VT, CH, LPR, U, LSTM>;
     if (l.lds > 48 * 1024) {
-        static bool raised = false;   // per instantiation; raising it twice is harmless
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               kMaxLdsBytes);
-            if (e != hipSuccess) return BS_ERR_HIP;
-            raised = true;
-        }
+        const int st_code = ensure_lds_limit(LdsKernelOf<kern>::reg, l.st);
+        if (st_code != BS_OK) return st_code;
     }
     if (l.ev_start || l.ev_stop)
         hipExtLaunchKernelGGL(kern, dim3(l.grid), dim3(l.threads), l.lds, l.st, l.ev_start,

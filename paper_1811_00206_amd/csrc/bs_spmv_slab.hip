@@ -88,14 +88,9 @@ __global__ __launch_bounds__(kSlabThreads) void spmv_slab_kernel(SpmvSlabArgs a)
 template <typename VT, int CH>
 int slab_launch_one(const SpmvSlabArgs& a, int grid, size_t lds, hipEvent_t e0, hipEvent_t e1,
                     hipStream_t st) {
-    auto kern = spmv_slab_kernel<VT, CH>;
-    static bool raised = false;   // per instantiation; raising it twice is harmless
-    if (!raised) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes) != hipSuccess)
-            return BS_ERR_HIP;
-        raised = true;
-    }
+    constexpr auto kern = spmv_slab_kernel<VT, CH>;
+    const int st_code = ensure_lds_limit(LdsKernelOf<kern>::reg, st);
+    if (st_code != BS_OK) return st_code;
     if (e0 || e1)
         hipExtLaunchKernelGGL(kern, dim3(grid), dim3(kSlabThreads), lds, st, e0, e1, 0, a);
     else

@@ -90,6 +90,9 @@ WORKLOADS = {w.name: w for w in [
     _mk(9, "conv5_n196", 512, 4608, 64, 16, 0.02, N=196),
     _mk(9, "conv4_n784", 512, 4608, 64, 16, 0.02, N=784),
     _mk(9, "conv2_n12544", 128, 576, 64, 16, 0.05, N=12544),
+    # the large-N end (Table 2's first rows, where the paper's kernel loses to dense):
+    # conv1_2, 64 x (64 * 3 * 3), one column per pixel of a 224 x 224 output
+    _mk(9, "conv1_n50176", 64, 576, 64, 16, 0.05, N=50176),
     # Table 4's axes on the LSTM gate matrix: balance range 25 / 50 / 100 at 60 % .. 80 %
     _mk(8, "lstm1500_b25_k10", 6000, 3000, 25, 10, 0.05),
     _mk(8, "lstm1500_b25_k5", 6000, 3000, 25, 5, 0.05),

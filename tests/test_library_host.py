@@ -88,6 +88,28 @@ def test_bad_arguments_are_refused_before_launch():
     assert lib.bs_reprune(p, p, 0, 4, 8, 4, 2, 3, p, p, null) == 2                  # k2 > k
 
 
+def test_first_use_inside_a_capture_has_its_own_status():
+    from paper_1811_00206_amd import binding as b
+    assert "bs_init" in b.bs_status_str(7)
+
+
+def test_probe_library_is_separate():
+    """The measurement helpers are not in the product library."""
+    from paper_1811_00206_amd import probe
+    lib = ctypes.CDLL(LIB)
+    plib = probe.load_library()
+    for n in probe.EXPORTS:
+        assert not hasattr(lib, n), n
+        assert getattr(plib, n) is not None
+    null = ctypes.c_void_p(0)
+    assert plib.bs_probe_empty(0, 256, null) == 2
+    assert plib.bs_probe_stream_read(null, 64, 0, null, null) == 1
+    assert plib.bs_probe_stream_read(ctypes.c_void_p(4096), 24, 0, null, null) == 2
+    assert plib.bs_probe_lds_gather(768, 1, 3, 64, null, null) == 2
+    assert plib.bs_probe_grid_barrier(257, 256, 10, 1500, 0, 100, ctypes.c_void_p(4096),
+                                      ctypes.c_void_p(4096), null) == 2
+
+
 def _plan_invariants(b, dtype, M, K, bank, k, N):
     """What the SpMM kernels assume about their launch, checked on the host for one shape."""
     vsize = 2 if dtype == b.BS_F16 else 4
