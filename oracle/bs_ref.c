@@ -23,7 +23,10 @@
  *     keep every element tied with T and break Sec. 3.1's equal count);
  *     among equal magnitudes the LOWER offset is kept; +a and -a tie.
  *   - kept entries are stored in ascending offset; values are bit copies.
- *   - offsets are bytes, so B <= 256; K must be a multiple of B.
+ *   - offsets are stored as bytes (B <= 256) or, in the entry points ending in _w, as
+ *     bytes or 16-bit words (B <= 65536: Sec. 3.1 leaves the balance range free, and
+ *     Sec. 4.1's 32 blocks per row exceed 256 for any K > 8192); K must be a multiple
+ *     of B.
  *   - NaN/Inf in W, x or X: rejected (BS_REF_ERR_NONFINITE).
  *
  * Arithmetic: every product and sum is done in double; one rounding to float
@@ -47,11 +50,27 @@ enum {
 
 /* ---------- shape checks ------------------------------------------------ */
 
-static int shape_ok(int64_t M, int64_t K, int B, int k)
+/* idx_bytes = 1: offsets are bytes, B <= 256; idx_bytes = 2: 16-bit offsets, B <= 65536 */
+static int shape_ok_w(int64_t M, int64_t K, int B, int k, int idx_bytes)
 {
-    if (M < 1 || K < 1 || B < 1 || B > 256 || k < 1 || k > B) return 0;
+    if (idx_bytes != 1 && idx_bytes != 2) return 0;
+    if (M < 1 || K < 1 || B < 1 || B > (idx_bytes == 1 ? 256 : 65536) || k < 1 || k > B) return 0;
     if (K % B != 0) return 0;
     return 1;
+}
+
+static int shape_ok(int64_t M, int64_t K, int B, int k) { return shape_ok_w(M, K, B, k, 1); }
+
+/* offset of stored entry e */
+static int offset_of(const void *idx, int idx_bytes, int64_t e)
+{
+    return idx_bytes == 1 ? (int)((const uint8_t *)idx)[e] : (int)((const uint16_t *)idx)[e];
+}
+
+static void set_offset(void *idx, int idx_bytes, int64_t e, int o)
+{
+    if (idx_bytes == 1) ((uint8_t *)idx)[e] = (uint8_t)o;
+    else ((uint16_t *)idx)[e] = (uint16_t)o;
 }
 
 /* ---------- IEEE binary16 decode, written out ---------------------------- */
@@ -91,68 +110,59 @@ static void bank_select(const double *mag, int B, int k, unsigned char *keep)
     }
 }
 
-int bs_ref_prune_pack_f32(const float *W, int64_t M, int64_t K, int B, int k,
-                          float *vals, uint8_t *idx)
+/*
+ * W and vals are fp32 (is_f16 = 0) or raw binary16 patterns (is_f16 = 1); idx holds
+ * bytes (idx_bytes = 1) or 16-bit words (idx_bytes = 2).  Values are copied bit for bit.
+ */
+int bs_ref_prune_pack_w(const void *W, int is_f16, int64_t M, int64_t K, int B, int k,
+                        void *vals, void *idx, int idx_bytes)
 {
     if (!W || !vals || !idx) return BS_REF_ERR_NULL;
-    if (!shape_ok(M, K, B, k)) return BS_REF_ERR_SHAPE;
+    if (!shape_ok_w(M, K, B, k, idx_bytes)) return BS_REF_ERR_SHAPE;
     int64_t nb = K / B;
-    double mag[256];
-    unsigned char keep[256];
-    for (int64_t r = 0; r < M; ++r) {
-        for (int64_t j = 0; j < nb; ++j) {
-            const float *bank = W + r * K + j * B;
+    double *mag = (double *)malloc((size_t)B * sizeof(double));
+    unsigned char *keep = (unsigned char *)malloc((size_t)B);
+    if (!mag || !keep) { free(mag); free(keep); return BS_REF_ERR_NULL; }
+    int st = BS_REF_OK;
+    for (int64_t r = 0; r < M && !st; ++r) {
+        for (int64_t j = 0; j < nb && !st; ++j) {
+            int64_t first = r * K + j * B;
             for (int o = 0; o < B; ++o) {
-                if (!isfinite(bank[o])) return BS_REF_ERR_NONFINITE;
-                mag[o] = fabs((double)bank[o]);
+                double v = is_f16 ? half_bits_to_double(((const uint16_t *)W)[first + o])
+                                  : (double)((const float *)W)[first + o];
+                if (!isfinite(v)) { st = BS_REF_ERR_NONFINITE; break; }
+                mag[o] = fabs(v);
             }
+            if (st) break;
             bank_select(mag, B, k, keep);
             int64_t out = (r * nb + j) * k;
             int t = 0;
             for (int o = 0; o < B; ++o) {
-                if (keep[o]) {
-                    memcpy(&vals[out + t], &bank[o], sizeof(float));
-                    idx[out + t] = (uint8_t)o;
-                    ++t;
-                }
+                if (!keep[o]) continue;
+                if (is_f16) ((uint16_t *)vals)[out + t] = ((const uint16_t *)W)[first + o];
+                else memcpy((float *)vals + out + t, (const float *)W + first + o, sizeof(float));
+                set_offset(idx, idx_bytes, out + t, o);
+                ++t;
             }
-            if (t != k) return BS_REF_ERR_SHAPE; /* cannot happen */
+            if (t != k) st = BS_REF_ERR_SHAPE; /* cannot happen */
         }
     }
-    return BS_REF_OK;
+    free(mag);
+    free(keep);
+    return st;
+}
+
+int bs_ref_prune_pack_f32(const float *W, int64_t M, int64_t K, int B, int k,
+                          float *vals, uint8_t *idx)
+{
+    return bs_ref_prune_pack_w(W, 0, M, K, B, k, vals, idx, 1);
 }
 
 /* binary16 storage: W and vals are raw 16-bit patterns */
 int bs_ref_prune_pack_f16(const uint16_t *W, int64_t M, int64_t K, int B, int k,
                           uint16_t *vals, uint8_t *idx)
 {
-    if (!W || !vals || !idx) return BS_REF_ERR_NULL;
-    if (!shape_ok(M, K, B, k)) return BS_REF_ERR_SHAPE;
-    int64_t nb = K / B;
-    double mag[256];
-    unsigned char keep[256];
-    for (int64_t r = 0; r < M; ++r) {
-        for (int64_t j = 0; j < nb; ++j) {
-            const uint16_t *bank = W + r * K + j * B;
-            for (int o = 0; o < B; ++o) {
-                double v = half_bits_to_double(bank[o]);
-                if (!isfinite(v)) return BS_REF_ERR_NONFINITE;
-                mag[o] = fabs(v);
-            }
-            bank_select(mag, B, k, keep);
-            int64_t out = (r * nb + j) * k;
-            int t = 0;
-            for (int o = 0; o < B; ++o) {
-                if (keep[o]) {
-                    vals[out + t] = bank[o];
-                    idx[out + t] = (uint8_t)o;
-                    ++t;
-                }
-            }
-            if (t != k) return BS_REF_ERR_SHAPE;
-        }
-    }
-    return BS_REF_OK;
+    return bs_ref_prune_pack_w(W, 1, M, K, B, k, vals, idx, 1);
 }
 
 /* ---------- re-prune a packed matrix to fewer weights per bank -----------
@@ -193,38 +203,35 @@ int bs_ref_reprune(const void *vals, int is_f16, const uint8_t *idx, int64_t n_b
 
 /* ---------- unpack: the pruned dense matrix M_p of Algorithm 1 ----------- */
 
-int bs_ref_unpack_f32(const float *vals, const uint8_t *idx, int64_t M, int64_t K,
-                      int B, int k, float *Wp)
+int bs_ref_unpack_w(const void *vals, int is_f16, const void *idx, int idx_bytes, int64_t M,
+                    int64_t K, int B, int k, void *Wp)
 {
     if (!vals || !idx || !Wp) return BS_REF_ERR_NULL;
-    if (!shape_ok(M, K, B, k)) return BS_REF_ERR_SHAPE;
+    if (!shape_ok_w(M, K, B, k, idx_bytes)) return BS_REF_ERR_SHAPE;
     int64_t nb = K / B;
-    memset(Wp, 0, (size_t)(M * K) * sizeof(float));
+    memset(Wp, 0, (size_t)(M * K) * (is_f16 ? sizeof(uint16_t) : sizeof(float)));
     for (int64_t r = 0; r < M; ++r)
         for (int64_t j = 0; j < nb; ++j)
             for (int t = 0; t < k; ++t) {
                 int64_t e = (r * nb + j) * k + t;
-                if (idx[e] >= B) return BS_REF_ERR_SHAPE;
-                memcpy(&Wp[r * K + j * B + idx[e]], &vals[e], sizeof(float));
+                int o = offset_of(idx, idx_bytes, e);
+                if (o >= B) return BS_REF_ERR_SHAPE;
+                if (is_f16) ((uint16_t *)Wp)[r * K + j * B + o] = ((const uint16_t *)vals)[e];
+                else memcpy((float *)Wp + r * K + j * B + o, (const float *)vals + e, sizeof(float));
             }
     return BS_REF_OK;
+}
+
+int bs_ref_unpack_f32(const float *vals, const uint8_t *idx, int64_t M, int64_t K,
+                      int B, int k, float *Wp)
+{
+    return bs_ref_unpack_w(vals, 0, idx, 1, M, K, B, k, Wp);
 }
 
 int bs_ref_unpack_f16(const uint16_t *vals, const uint8_t *idx, int64_t M, int64_t K,
                       int B, int k, uint16_t *Wp)
 {
-    if (!vals || !idx || !Wp) return BS_REF_ERR_NULL;
-    if (!shape_ok(M, K, B, k)) return BS_REF_ERR_SHAPE;
-    int64_t nb = K / B;
-    memset(Wp, 0, (size_t)(M * K) * sizeof(uint16_t));
-    for (int64_t r = 0; r < M; ++r)
-        for (int64_t j = 0; j < nb; ++j)
-            for (int t = 0; t < k; ++t) {
-                int64_t e = (r * nb + j) * k + t;
-                if (idx[e] >= B) return BS_REF_ERR_SHAPE;
-                Wp[r * K + j * B + idx[e]] = vals[e];
-            }
-    return BS_REF_OK;
+    return bs_ref_unpack_w(vals, 1, idx, 1, M, K, B, k, Wp);
 }
 
 /* ---------- sparse products (Fig. 3; eq. (1) with zero bias) ------------- */
@@ -235,7 +242,7 @@ int bs_ref_unpack_f16(const uint16_t *vals, const uint8_t *idx, int64_t M, int64
  * banks ascending, slots ascending.  is_f16 selects the storage type of vals.
  * X is K x N row-major with leading dimension ldx.
  */
-static int row_dot_f64(const void *vals, int is_f16, const uint8_t *idx,
+static int row_dot_f64(const void *vals, int is_f16, const void *idx, int idx_bytes,
                        int64_t K, int B, int k, const float *X, int64_t ldx,
                        int64_t r, int64_t n, double *out)
 {
@@ -246,8 +253,9 @@ static int row_dot_f64(const void *vals, int is_f16, const uint8_t *idx,
             int64_t e = (r * nb + j) * k + t;
             double w = is_f16 ? half_bits_to_double(((const uint16_t *)vals)[e])
                               : (double)((const float *)vals)[e];
-            if (idx[e] >= B) return BS_REF_ERR_SHAPE;
-            double xv = (double)X[(j * B + idx[e]) * ldx + n];
+            int o = offset_of(idx, idx_bytes, e);
+            if (o >= B) return BS_REF_ERR_SHAPE;
+            double xv = (double)X[(j * B + o) * ldx + n];
             if (!isfinite(w) || !isfinite(xv)) return BS_REF_ERR_NONFINITE;
             acc += w * xv;
         }
@@ -256,36 +264,43 @@ static int row_dot_f64(const void *vals, int is_f16, const uint8_t *idx,
     return BS_REF_OK;
 }
 
-static int spmm_check(const void *vals, const uint8_t *idx, int64_t M, int64_t K,
+static int spmm_check(const void *vals, const void *idx, int idx_bytes, int64_t M, int64_t K,
                       int B, int k, const float *X, int64_t N, int64_t ldx,
                       const void *Y, int64_t ldy)
 {
     if (!vals || !idx || !X || !Y) return BS_REF_ERR_NULL;
-    if (!shape_ok(M, K, B, k)) return BS_REF_ERR_SHAPE;
+    if (!shape_ok_w(M, K, B, k, idx_bytes)) return BS_REF_ERR_SHAPE;
     if (N < 1 || ldx < N || ldy < N) return BS_REF_ERR_SHAPE;
     return BS_REF_OK;
 }
 
 /* double-precision outputs: the un-rounded sums (used by the exactness pins) */
+int bs_ref_spmm_f64_w(const void *vals, int is_f16, const void *idx, int idx_bytes, int64_t M,
+                      int64_t K, int B, int k, const float *X, int64_t N,
+                      int64_t ldx, double *Yd, int64_t ldy)
+{
+    int st = spmm_check(vals, idx, idx_bytes, M, K, B, k, X, N, ldx, Yd, ldy);
+    if (st) return st;
+    for (int64_t r = 0; r < M; ++r)
+        for (int64_t n = 0; n < N; ++n) {
+            st = row_dot_f64(vals, is_f16, idx, idx_bytes, K, B, k, X, ldx, r, n, &Yd[r * ldy + n]);
+            if (st) return st;
+        }
+    return BS_REF_OK;
+}
+
 int bs_ref_spmm_f64(const void *vals, int is_f16, const uint8_t *idx, int64_t M,
                     int64_t K, int B, int k, const float *X, int64_t N,
                     int64_t ldx, double *Yd, int64_t ldy)
 {
-    int st = spmm_check(vals, idx, M, K, B, k, X, N, ldx, Yd, ldy);
-    if (st) return st;
-    for (int64_t r = 0; r < M; ++r)
-        for (int64_t n = 0; n < N; ++n) {
-            st = row_dot_f64(vals, is_f16, idx, K, B, k, X, ldx, r, n, &Yd[r * ldy + n]);
-            if (st) return st;
-        }
-    return BS_REF_OK;
+    return bs_ref_spmm_f64_w(vals, is_f16, idx, 1, M, K, B, k, X, N, ldx, Yd, ldy);
 }
 
 /* ---- row-split threading: rows are independent, per-row arithmetic is the
  *      same code, so the result is identical for any thread count ---------- */
 
 typedef struct {
-    const void *vals; int is_f16; const uint8_t *idx;
+    const void *vals; int is_f16; const void *idx; int idx_bytes;
     int64_t K; int B; int k;
     const float *X; int64_t N; int64_t ldx;
     float *Y; int64_t ldy; int64_t r0; int64_t r1; int status;
@@ -298,7 +313,7 @@ static void *spmm_job_run(void *arg)
     for (int64_t r = jb->r0; r < jb->r1; ++r)
         for (int64_t n = 0; n < jb->N; ++n) {
             double acc;
-            int st = row_dot_f64(jb->vals, jb->is_f16, jb->idx, jb->K, jb->B, jb->k,
+            int st = row_dot_f64(jb->vals, jb->is_f16, jb->idx, jb->idx_bytes, jb->K, jb->B, jb->k,
                                  jb->X, jb->ldx, r, n, &acc);
             if (st) { jb->status = st; return NULL; }
             jb->Y[r * jb->ldy + n] = (float)acc; /* the single rounding */
@@ -309,11 +324,11 @@ static void *spmm_job_run(void *arg)
 /*
  * Y = fp32( W_sparse . X ), accumulated in double.  threads <= 1 runs inline.
  */
-int bs_ref_spmm(const void *vals, int is_f16, const uint8_t *idx, int64_t M,
-                int64_t K, int B, int k, const float *X, int64_t N, int64_t ldx,
-                float *Y, int64_t ldy, int threads)
+int bs_ref_spmm_w(const void *vals, int is_f16, const void *idx, int idx_bytes, int64_t M,
+                  int64_t K, int B, int k, const float *X, int64_t N, int64_t ldx,
+                  float *Y, int64_t ldy, int threads)
 {
-    int st = spmm_check(vals, idx, M, K, B, k, X, N, ldx, Y, ldy);
+    int st = spmm_check(vals, idx, idx_bytes, M, K, B, k, X, N, ldx, Y, ldy);
     if (st) return st;
     if (threads < 1) threads = 1;
     if (threads > 256) threads = 256;
@@ -321,7 +336,7 @@ int bs_ref_spmm(const void *vals, int is_f16, const uint8_t *idx, int64_t M,
     spmm_job jobs[256];
     pthread_t tid[256];
     for (int t = 0; t < threads; ++t) {
-        spmm_job jb = { vals, is_f16, idx, K, B, k, X, N, ldx, Y, ldy,
+        spmm_job jb = { vals, is_f16, idx, idx_bytes, K, B, k, X, N, ldx, Y, ldy,
                         M * t / threads, M * (t + 1) / threads, 0 };
         jobs[t] = jb;
     }
@@ -340,6 +355,13 @@ int bs_ref_spmm(const void *vals, int is_f16, const uint8_t *idx, int64_t M,
         if (jobs[t].status && !st) st = jobs[t].status;
     }
     return st;
+}
+
+int bs_ref_spmm(const void *vals, int is_f16, const uint8_t *idx, int64_t M,
+                int64_t K, int B, int k, const float *X, int64_t N, int64_t ldx,
+                float *Y, int64_t ldy, int threads)
+{
+    return bs_ref_spmm_w(vals, is_f16, idx, 1, M, K, B, k, X, N, ldx, Y, ldy, threads);
 }
 
 /* y = fp32( W_sparse . x ): the N = 1 case of the definition above */
@@ -381,7 +403,7 @@ int bs_ref_lstm_step(const void *vals, int is_f16, const uint8_t *idx, int64_t H
     for (int64_t u = 0; u < H && !st; ++u) {
         double a[4];
         for (int g = 0; g < 4 && !st; ++g) {
-            st = row_dot_f64(vals, is_f16, idx, K, B, k, xh, 1, g * H + u, 0, &a[g]);
+            st = row_dot_f64(vals, is_f16, idx, 1, K, B, k, xh, 1, g * H + u, 0, &a[g]);
             if (!isfinite((double)bias[g * H + u])) st = BS_REF_ERR_NONFINITE;
             a[g] += (double)bias[g * H + u];
         }

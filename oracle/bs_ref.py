@@ -47,12 +47,11 @@ def _load():
         build()
         lib = ctypes.CDLL(_LIB)
         i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
-        lib.bs_ref_prune_pack_f32.argtypes = [vp, i64, i64, i32, i32, vp, vp]
-        lib.bs_ref_prune_pack_f16.argtypes = [vp, i64, i64, i32, i32, vp, vp]
-        lib.bs_ref_unpack_f32.argtypes = [vp, vp, i64, i64, i32, i32, vp]
-        lib.bs_ref_unpack_f16.argtypes = [vp, vp, i64, i64, i32, i32, vp]
-        lib.bs_ref_spmm_f64.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, i64, i64, vp, i64]
-        lib.bs_ref_spmm.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, i64, i64, vp, i64, i32]
+        # the _w entry points take the width of a stored offset (1 or 2 bytes)
+        lib.bs_ref_prune_pack_w.argtypes = [vp, i32, i64, i64, i32, i32, vp, vp, i32]
+        lib.bs_ref_unpack_w.argtypes = [vp, i32, vp, i32, i64, i64, i32, i32, vp]
+        lib.bs_ref_spmm_f64_w.argtypes = [vp, i32, vp, i32, i64, i64, i32, i32, vp, i64, i64, vp, i64]
+        lib.bs_ref_spmm_w.argtypes = [vp, i32, vp, i32, i64, i64, i32, i32, vp, i64, i64, vp, i64, i32]
         lib.bs_ref_spmv.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, vp, i32]
         lib.bs_ref_dense_gemm_f64.argtypes = [vp, i32, i64, i64, vp, i64, i64, vp, i64]
         lib.bs_ref_reprune.argtypes = [vp, i32, vp, i64, i32, i32, vp, vp]
@@ -84,20 +83,27 @@ def host_threads() -> int:
         return os.cpu_count() or 1
 
 
-def prune_pack(W: np.ndarray, bank: int, k: int):
+def _offsets(idx: np.ndarray):
+    """(bytes per stored offset, contiguous array) for a uint8 or uint16 offset array."""
+    if idx.dtype == np.uint8 or idx.dtype == np.uint16:
+        return idx.dtype.itemsize, np.ascontiguousarray(idx)
+    raise TypeError(f"idx must be uint8 or uint16, got {idx.dtype}")
+
+
+def prune_pack(W: np.ndarray, bank: int, k: int, wide: bool = False):
     """W (M x K, fp32 or fp16) -> vals [M, K/bank, k] (same dtype, bit copies),
-    idx [M, K/bank, k] uint8, ascending offsets inside each bank."""
+    idx [M, K/bank, k], ascending offsets inside each bank: uint8 (bank <= 256), or
+    with wide=True uint16 (bank <= 65536)."""
     is16, W = _storage(W, "W")
     if W.ndim != 2:
         raise ValueError("W must be 2-D")
     M, K = W.shape
-    if bank < 1 or K % bank or k < 1 or k > bank or bank > 256:
+    if bank < 1 or K % bank or k < 1 or k > bank or bank > (65536 if wide else 256):
         raise OracleError(ERR_SHAPE, "prune_pack")
     nb = K // bank
     vals = np.empty((M, nb, k), dtype=W.dtype)
-    idx = np.empty((M, nb, k), dtype=np.uint8)
-    fn = _load().bs_ref_prune_pack_f16 if is16 else _load().bs_ref_prune_pack_f32
-    st = fn(_p(W), M, K, bank, k, _p(vals), _p(idx))
+    idx = np.empty((M, nb, k), dtype=np.uint16 if wide else np.uint8)
+    st = _load().bs_ref_prune_pack_w(_p(W), is16, M, K, bank, k, _p(vals), _p(idx), idx.dtype.itemsize)
     if st:
         raise OracleError(st, "prune_pack")
     return vals, idx
@@ -106,12 +112,11 @@ def prune_pack(W: np.ndarray, bank: int, k: int):
 def unpack(vals: np.ndarray, idx: np.ndarray, bank: int) -> np.ndarray:
     """Packed form -> the pruned dense matrix (zeros elsewhere)."""
     is16, vals = _storage(vals, "vals")
-    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    ib, idx = _offsets(idx)
     M, nb, k = vals.shape
     K = nb * bank
     Wp = np.empty((M, K), dtype=vals.dtype)
-    fn = _load().bs_ref_unpack_f16 if is16 else _load().bs_ref_unpack_f32
-    st = fn(_p(vals), _p(idx), M, K, bank, k, _p(Wp))
+    st = _load().bs_ref_unpack_w(_p(vals), is16, _p(idx), ib, M, K, bank, k, _p(Wp))
     if st:
         raise OracleError(st, "unpack")
     return Wp
@@ -127,13 +132,13 @@ def _x2d(X: np.ndarray, K: int):
 def spmm_f64(vals, idx, bank: int, X) -> np.ndarray:
     """Un-rounded double sums of the sparse product (for exactness pins)."""
     is16, vals = _storage(vals, "vals")
-    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    ib, idx = _offsets(idx)
     M, nb, k = vals.shape
     K = nb * bank
     vec, X2 = _x2d(X, K)
     N = X2.shape[1]
     Yd = np.empty((M, N), dtype=np.float64)
-    st = _load().bs_ref_spmm_f64(_p(vals), is16, _p(idx), M, K, bank, k, _p(X2), N, N, _p(Yd), N)
+    st = _load().bs_ref_spmm_f64_w(_p(vals), is16, _p(idx), ib, M, K, bank, k, _p(X2), N, N, _p(Yd), N)
     if st:
         raise OracleError(st, "spmm_f64")
     return Yd[:, 0] if vec else Yd
@@ -142,14 +147,14 @@ def spmm_f64(vals, idx, bank: int, X) -> np.ndarray:
 def spmm(vals, idx, bank: int, X, threads: int = 1) -> np.ndarray:
     """Y = fp32(W_sparse . X); X is [K, N] (or [K] for the matrix-vector case)."""
     is16, vals = _storage(vals, "vals")
-    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    ib, idx = _offsets(idx)
     M, nb, k = vals.shape
     K = nb * bank
     vec, X2 = _x2d(X, K)
     N = X2.shape[1]
     Y = np.empty((M, N), dtype=np.float32)
-    st = _load().bs_ref_spmm(_p(vals), is16, _p(idx), M, K, bank, k, _p(X2), N, N, _p(Y), N,
-                             int(threads))
+    st = _load().bs_ref_spmm_w(_p(vals), is16, _p(idx), ib, M, K, bank, k, _p(X2), N, N, _p(Y), N,
+                               int(threads))
     if st:
         raise OracleError(st, "spmm")
     return Y[:, 0] if vec else Y
@@ -158,12 +163,16 @@ def spmm(vals, idx, bank: int, X, threads: int = 1) -> np.ndarray:
 def spmv(vals, idx, bank: int, x, threads: int = 1) -> np.ndarray:
     """y = fp32(W_sparse . x)."""
     is16, vals = _storage(vals, "vals")
-    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    ib, idx = _offsets(idx)
     M, nb, k = vals.shape
     K = nb * bank
     x = np.ascontiguousarray(x, dtype=np.float32).reshape(K)
     y = np.empty(M, dtype=np.float32)
-    st = _load().bs_ref_spmv(_p(vals), is16, _p(idx), M, K, bank, k, _p(x), _p(y), int(threads))
+    if ib == 1:
+        st = _load().bs_ref_spmv(_p(vals), is16, _p(idx), M, K, bank, k, _p(x), _p(y), int(threads))
+    else:   # the N = 1 case of the product with 16-bit offsets
+        st = _load().bs_ref_spmm_w(_p(vals), is16, _p(idx), ib, M, K, bank, k, _p(x), 1, 1, _p(y), 1,
+                                   int(threads))
     if st:
         raise OracleError(st, "spmv")
     return y

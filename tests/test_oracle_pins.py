@@ -441,3 +441,87 @@ def test_reprune_ties_and_library_definition():
     assert np.take_along_axis(idx, slots, axis=2).tobytes() == i2.tobytes()
     with pytest.raises(bs_ref.OracleError):
         bs_ref.reprune(vals, idx, 13)        # cannot grow
+
+
+# ------------------------------------------- balance ranges over 256: 16-bit offsets
+# Sec. 3.1 leaves the balance range free; Sec. 4.1's 32 blocks per row give banks over 256
+# for any K > 8192.  The same pins as above, on banks a byte cannot index.
+
+def argsort_topk_wide(W, bank, k):
+    vals, off = argsort_topk(W, bank, k)      # offsets were narrowed to uint8 there: redo them
+    M, K = W.shape
+    Wb = W.reshape(M, K // bank, bank)
+    order = np.argsort(-np.abs(Wb.astype(np.float64)), axis=2, kind="stable")[:, :, :k]
+    return np.take_along_axis(Wb, np.sort(order, axis=2), axis=2), np.sort(order, axis=2).astype(np.uint16)
+
+
+WIDE_SHAPES = [(3, 1024, 512, 7), (2, 600, 300, 299), (1, 2048, 2048, 100), (5, 1542, 257, 1),
+               (2, 8192, 1024, 128), (4, 64, 16, 4)]
+
+
+@pytest.mark.parametrize("M,K,bank,k", WIDE_SHAPES)
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_wide_offsets_match_stable_argsort_and_invariants(M, K, bank, k, dtype):
+    W = rand_w(M, K, 51, dtype)
+    vals, idx = bs_ref.prune_pack(W, bank, k, wide=True)
+    assert idx.dtype == np.uint16 and vals.shape == idx.shape == (M, K // bank, k)
+    assert (idx < bank).all()
+    if k > 1:
+        assert (np.diff(idx.astype(np.int32), axis=2) > 0).all()
+    v2, i2 = argsort_topk_wide(W, bank, k)
+    assert idx.tobytes() == i2.tobytes() and vals.tobytes() == v2.tobytes()
+
+
+def test_wide_offsets_ties_and_high_offsets():
+    # all magnitudes equal: the k lowest offsets stay, whatever the signs
+    W = np.full((2, 600), 0.5, dtype=np.float32)
+    W[:, ::3] *= -1
+    vals, idx = bs_ref.prune_pack(W, 300, 40, wide=True)
+    assert (idx == np.arange(40, dtype=np.uint16)).all()
+    # the only large elements sit past offset 255: their offsets need the high byte
+    W = np.zeros((1, 1000), dtype=np.float32)
+    W[0, [256, 511, 999]] = [3.0, -2.0, 1.0]
+    vals, idx = bs_ref.prune_pack(W, 1000, 3, wide=True)
+    assert idx.ravel().tolist() == [256, 511, 999] and vals.ravel().tolist() == [3.0, -2.0, 1.0]
+    vals, idx = bs_ref.prune_pack(W, 1000, 1, wide=True)
+    assert idx.ravel().tolist() == [int(np.argmax(np.abs(W[0])))]
+    # a tie at the cut drops the higher offset
+    W = np.zeros((1, 512), dtype=np.float32)
+    W[0, [300, 400, 500]] = [1.0, -1.0, 1.0]
+    vals, idx = bs_ref.prune_pack(W, 512, 2, wide=True)
+    assert idx.ravel().tolist() == [300, 400]
+    # byte offsets refuse such banks, and 16-bit ones stop at 65536
+    with pytest.raises(bs_ref.OracleError):
+        bs_ref.prune_pack(W, 512, 2)
+    with pytest.raises(bs_ref.OracleError):
+        bs_ref.prune_pack(np.zeros((1, 131072), dtype=np.float32), 131072, 2, wide=True)
+
+
+@pytest.mark.parametrize("M,K,bank,k", WIDE_SHAPES)
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_wide_offsets_products_equal_dense_product_of_the_unpacked_matrix(M, K, bank, k, dtype):
+    W = rand_w(M, K, 52, dtype, sigma=0.05)
+    vals, idx = bs_ref.prune_pack(W, bank, k, wide=True)
+    # unpack against a numpy scatter
+    Wp = bs_ref.unpack(vals, idx, bank)
+    Wp_np = np.zeros((M, K // bank, bank), dtype=W.dtype)
+    np.put_along_axis(Wp_np, idx.astype(np.int64), vals, axis=2)
+    assert Wp.tobytes() == Wp_np.reshape(M, K).tobytes()
+    for N in (1, 3):
+        X = workloads.draw_activations(K, N, 52)
+        Yd = bs_ref.spmm_f64(vals, idx, bank, X)
+        ref = Wp.astype(np.float64) @ X.astype(np.float64).reshape(K, -1)
+        assert np.allclose(Yd.reshape(M, -1), ref, rtol=1e-12, atol=1e-300)
+        assert (bs_ref.dense_gemm_f64(Wp, X).reshape(M, -1) == Yd.reshape(M, -1)).all()   # exact in fp64
+        Y = bs_ref.spmm(vals, idx, bank, X, threads=3)
+        assert Y.reshape(M, -1).tobytes() == Yd.reshape(M, -1).astype(np.float32).tobytes()
+    x = workloads.draw_activations(K, 1, 53)
+    assert bs_ref.spmv(vals, idx, bank, x).tobytes() == bs_ref.spmm(vals, idx, bank, x).tobytes()
+
+
+def test_wide_and_byte_offsets_agree_where_both_apply():
+    W = rand_w(9, 768, 54)
+    for bank, k in [(256, 30), (64, 5), (3, 2)]:
+        v8, i8 = bs_ref.prune_pack(W, bank, k)
+        v16, i16 = bs_ref.prune_pack(W, bank, k, wide=True)
+        assert v8.tobytes() == v16.tobytes() and (i8.astype(np.uint16) == i16).all()
