@@ -8,10 +8,15 @@ one-time, model-load step; it is timed separately and reported under
 ``extras``).  The default workload is the LSTM-1500 gate matrix, 6000 x 3000,
 banks of 100 keeping 10 (90 % sparse), batch 1.
 
-The timed region is exactly K steps between two HIP events on the launch
-stream; ``value`` and ``roofline.achieved`` are both algorithmic bytes x K /
-that wall time (gaps between launches included, so the kernel's own duration is
-at most this).
+The timed region is exactly K steps on the launch stream, captured into one HIP
+graph together with a short pre-roll and two one-lane kernels that store the
+GPU's wall clock right before the first and right after the last of the K
+launches (events cannot be recorded inside a captured graph on this runtime, and
+events around the replay also time the launching of the graph itself: 8 us, which
+is 10 % of a 20-step region and nothing of a 2000-step one).  ``value`` and
+``roofline.achieved`` are both algorithmic bytes x K / that time (gaps between
+launches included, so the kernel's own duration is at most this); the time of
+the whole replay between two HIP events is reported beside it.
 "Cold" (default): the launches rotate over enough copies of vals/idx to exceed
 twice the 256 MB last-level cache, and a 768 MB streaming read of unrelated
 memory is enqueued right before every timed replay, so no timed launch finds its
@@ -57,6 +62,13 @@ def parse():
     ap.add_argument("--eager", action="store_true", help="time Python-side launches, no HIP graph")
     ap.add_argument("--no-extras", action="store_true", help="skip the secondary measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--copies", type=int, default=0,
+                    help="rotate over this many copies of the packed matrix (default: enough to exceed "
+                         "twice the last-level cache)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line: time bs_spmv_ex on --workload over launch shapes "
+                         "(lanes per row x rows per workgroup), cold, same protocol, plus empty kernels and "
+                         "read-only kernels of several shapes; prints one JSON object")
     ap.add_argument("--only", default="", help="comma-separated other workloads to measure under extras "
                                                "(default: all of them)")
     return ap.parse_args()
@@ -123,49 +135,89 @@ class Evictor:
         self.probe.probe_stream_read(self.buf)
 
 
-def capture(torch, fn, n, what):
-    """n calls of fn captured into one graph (after an eager warm-up call on a side stream) and
-    replayed once, untimed.  None if the calls cannot be captured (recorded in EAGER_FALLBACKS)."""
-    try:
-        side = torch.cuda.Stream()
-        with torch.cuda.stream(side):
-            fn(0)
+class GraphTimer:
+    """Times n calls of a function inside one captured graph with the GPU's own wall clock:
+    graph = [pre-roll calls] [stamp] [the n calls] [stamp].  The pre-roll (calls n, n+1, ... of
+    the same function, i.e. other copies of the data when the caller rotates) brings the
+    machine to its steady state; the stamps are one-lane kernels that store the constant-rate
+    wall clock (100 MHz here), so launching the graph is not inside the interval.  The interval
+    of two stamps with nothing between them is measured once and subtracted."""
+
+    PREROLL = 32
+
+    def __init__(self, torch, probe, dev):
+        self.torch, self.probe = torch, probe
+        self.slots = torch.zeros(8, dtype=torch.int64, device=dev)
+        self.khz = probe.wall_clock_khz()
+        self.gap_us = 0.0
+        if self.khz > 0:
+            # two adjacent stamps behind a pre-roll of empty kernels (the steady state the
+            # timed launches see; the first launches of a replay are slower)
+            g = self._capture(lambda i: probe.probe_empty(1, 64), 0, self.PREROLL, "stamp gap")
+            if g is not None:
+                self.gap_us = min(self._replay(g, None)[0] for _ in range(5))
+
+    def _capture(self, fn, n, preroll, what):
+        torch = self.torch
+        try:
+            if n or preroll:
+                side = torch.cuda.Stream()
+                with torch.cuda.stream(side):
+                    fn(0)
+                torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for i in range(preroll):
+                    fn(n + i)
+                self.probe.probe_timestamp(self.slots, 0)
+                for i in range(n):
+                    fn(i)
+                self.probe.probe_timestamp(self.slots, 1)
+            g.replay()
+            torch.cuda.synchronize()
+            return g
+        except Exception as exc:
+            torch.cuda.synchronize()
+            EAGER_FALLBACKS.append(f"{what}: {str(exc)[:120]}")
+            print(f"bench.py: graph capture failed for {what!r} ({exc}); timing eager launches",
+                  file=sys.stderr)
+            return None
+
+    def _replay(self, g, evict):
+        """(us between the two stamps, us between two events around the whole replay)"""
+        torch = self.torch
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            for i in range(n):
-                fn(i)
+        if evict is not None:
+            evict()
+        s.record()
         g.replay()
+        e.record()
         torch.cuda.synchronize()
-        return g
-    except Exception as exc:
-        torch.cuda.synchronize()
-        EAGER_FALLBACKS.append(f"{what}: {str(exc)[:120]}")
-        print(f"bench.py: graph capture failed for {what!r} ({exc}); timing eager launches",
-              file=sys.stderr)
-        return None
+        t0, t1 = self.slots[:2].tolist()
+        return (t1 - t0) / self.khz * 1e3, s.elapsed_time(e) * 1e3
 
+    def capture(self, fn, n, what, preroll=None):
+        """A graph of n timed calls (after a pre-roll), replayed once untimed; None if the calls
+        cannot be captured or the wall clock's rate is unknown."""
+        if self.khz <= 0:
+            return None
+        pre = self.PREROLL if preroll is None else preroll
+        g = self._capture(fn, n, pre, what)
+        return None if g is None else (g, n, pre)
 
-def timed_replay_us(torch, g, n, evict=None):
-    """One replay of a captured graph of n calls between two events; `evict` is enqueued first."""
-    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    if evict is not None:
-        evict()
-    s.record()
-    g.replay()
-    e.record()
-    torch.cuda.synchronize()
-    return s.elapsed_time(e) * 1e3 / n
+    def replay_us(self, cap, evict=None):
+        """One replay: (us per timed call by the stamps, us per call of the whole replay by events)."""
+        g, n, pre = cap
+        stamps, events = self._replay(g, evict)
+        return max(stamps - self.gap_us, 0.0) / n, events / (n + pre)
 
-
-def graph_us(torch, fn, n, what, evict=None):
-    """Time per call of n calls captured into one graph and replayed: the protocol of `value`,
-    free of the host's per-call cost (which would inflate kernels of a few microseconds)."""
-    g = capture(torch, fn, n, what)
-    if g is None:
-        return region_us(torch, fn, n)
-    return timed_replay_us(torch, g, n, evict)
+    def us(self, fn, n, what, evict=None, preroll=8, best_of=1):
+        """Time per call of n calls; falls back to eager launches between events."""
+        cap = self.capture(fn, n, what, preroll)
+        if cap is None:
+            return region_us(self.torch, fn, n)
+        return min(self.replay_us(cap, evict)[0] for _ in range(best_of))
 
 
 OTHER_WORKLOADS = ("tiny", "sweep_k32", "sweep_k16", "sweep_k8", "sweep_k4", "sweep_k2",
@@ -178,7 +230,9 @@ OTHER_WORKLOADS = ("tiny", "sweep_k32", "sweep_k16", "sweep_k8", "sweep_k4", "sw
                    "conv5_n196", "conv4_n784", "conv2_n12544", "conv1_n50176",
                    # Sec. 4.1's matrix shape, 50 % .. 97 % sparse, batch 1 and 8
                    "bench16k_k128", "bench16k_k64", "bench16k_k32", "bench16k_k16", "bench16k_k8",
-                   "bench16k_k128_n8", "bench16k_k32_n8", "bench16k_k8_n8")
+                   "bench16k_k128_n8", "bench16k_k32_n8", "bench16k_k8_n8",
+                   # balance ranges over 256 (16-bit offsets): 16 and 8 banks per row
+                   "bench16k_b512_k64", "bench16k_b1024_k128", "bench16k_b512_k64_n8")
 
 
 def rotation(alg_bytes):
@@ -186,13 +240,16 @@ def rotation(alg_bytes):
     return max(2, -(-2 * LLC_BYTES // alg_bytes) + 1)
 
 
-def quick_measure(torch, np, bs, workloads, dev, name, o_time, evict, launches=200):
+def quick_measure(torch, np, bs, workloads, dev, name, o_time, evict, timer, launches=200):
     """One workload, cold, `launches` graph-replayed launches: time per launch.
     o_time = measured launch floor, for eq. (5)'s ideal time."""
     wl, W, X = workloads.make(name)
+    wide = wl.idx_bytes == 2            # balance range over 256: the calls with 16-bit offsets
+    prune, spmv_call, spmm_call = ((bs.bs_prune_pack_wide, bs.bs_spmv_wide, bs.bs_spmm_wide) if wide else
+                                   (bs.bs_prune_pack, bs.bs_spmv, bs.bs_spmm))
     Wd = torch.from_numpy(W).to(dev)
     Xd = torch.from_numpy(np.ascontiguousarray(X)).to(dev)
-    vals, idx = bs.bs_prune_pack(Wd, wl.bank, wl.k)
+    vals, idx = prune(Wd, wl.bank, wl.k)
     alg = wl.spmv_bytes()
     R = rotation(alg)
     copies = [(vals, idx)] + [(vals.clone(), idx.clone()) for _ in range(R - 1)]
@@ -200,13 +257,16 @@ def quick_measure(torch, np, bs, workloads, dev, name, o_time, evict, launches=2
     Y = torch.empty((wl.M, wl.N) if spmm else (wl.M,), dtype=torch.float32, device=dev)
     if spmm:
         code = bs.BS_F16 if wl.dtype == "f16" else bs.BS_F32
-        ws = torch.zeros(max(16, bs.bs_spmm_workspace_bytes(code, wl.M, wl.K, wl.bank, wl.k, wl.N)),
-                         dtype=torch.uint8, device=dev)
-        fn = lambda i: bs.bs_spmm(copies[i % R][0], copies[i % R][1], wl.bank, Xd, out=Y, workspace=ws)
+        need = (bs.bs_spmm_workspace_bytes_wide if wide else bs.bs_spmm_workspace_bytes)(
+            code, wl.M, wl.K, wl.bank, wl.k, wl.N)
+        ws = torch.zeros(max(16, need), dtype=torch.uint8, device=dev)
+        fn = lambda i: spmm_call(copies[i % R][0], copies[i % R][1], wl.bank, Xd, out=Y, workspace=ws)
+    elif wide:
+        fn = lambda i: spmv_call(copies[i % R][0], copies[i % R][1], wl.bank, Xd, out=Y)
     else:
         cs = [bs.PreparedSpmv(v, ix, wl.bank, Xd, Y) for v, ix in copies]
         fn = lambda i: cs[i % R]()
-    us = graph_us(torch, fn, launches, name, evict)
+    us = timer.us(fn, launches, name, evict)
     res = {"us": round(us, 2), "GBps": round(alg / us / 1e3, 1),
            "frac_of_8TBps": round(alg / us / 1e3 / HBM_PEAK_GBS, 3)}
     if spmm:
@@ -220,7 +280,7 @@ def quick_measure(torch, np, bs, workloads, dev, name, o_time, evict, launches=2
     n_d = 10 if spmm else 50
     dfn = (lambda i: bs.bs_dense_gemm(Wc[i % len(Wc)], Xd, out=Y)) if spmm else \
           (lambda i: bs.bs_dense_gemv(Wc[i % len(Wc)], Xd, out=Y))
-    d_us = graph_us(torch, dfn, n_d, name + " dense", evict)
+    d_us = timer.us(dfn, n_d, name + " dense", evict)
     lib_us = None
     try:
         Xl = Xd if wl.dtype == "f32" else Xd.half()
@@ -228,7 +288,7 @@ def quick_measure(torch, np, bs, workloads, dev, name, o_time, evict, launches=2
         lib = lambda i: torch.matmul(Wc[i % len(Wc)], Xl, out=Yl)
         for i in range(3):
             lib(i)
-        lib_us = graph_us(torch, lib, n_d, name + " dense (vendor library)", evict)
+        lib_us = timer.us(lib, n_d, name + " dense (vendor library)", evict)
     except Exception as exc:
         res["dense_library_error"] = str(exc)[:80]
     res["speedup_vs_faster_dense"] = round(min(d_us, lib_us if lib_us else d_us) / us, 2)
@@ -240,10 +300,10 @@ def quick_measure(torch, np, bs, workloads, dev, name, o_time, evict, launches=2
     res["ideal_us_eq5"] = round(max(d_us - o_time, 0.0) * (1 - wl.sparsity) + o_time, 2)
     # pruning + packing this matrix (W rotates as for the dense baseline)
     p_out = (torch.empty_like(vals), torch.empty_like(idx))
-    pfn = lambda i: bs.bs_prune_pack(Wc[i % len(Wc)], wl.bank, wl.k, out=p_out)
-    p_us = graph_us(torch, pfn, 6, name + " prune_pack", evict)
+    pfn = lambda i: prune(Wc[i % len(Wc)], wl.bank, wl.k, out=p_out)
+    p_us = timer.us(pfn, 6, name + " prune_pack", evict, preroll=2)
     res["prune_pack_us"] = round(p_us, 1)
-    res["prune_pack_GBps"] = round((W.nbytes + wl.nnz * (wl.val_bytes + 1)) / p_us / 1e3, 1)
+    res["prune_pack_GBps"] = round((W.nbytes + wl.nnz * (wl.val_bytes + wl.idx_bytes)) / p_us / 1e3, 1)
     return res
 
 
@@ -255,6 +315,64 @@ def spmv_kernel_name(bs, wl):
         return "spmv_slab_kernel", p
     vt = "__half" if wl.dtype == "f16" else "float"
     return f"spmv_kernel<{vt},{p['ch']},{p['lpr']},{p['u']}>", p
+
+
+def sweep(args, torch, np, bs, probe, workloads, dev):
+    """Launch-shape sweep of bs_spmv_ex on one workload, cold, graph of 400 launches, best of 3."""
+    wl, W, X = workloads.make(args.workload)
+    Wd = torch.from_numpy(W).to(dev)
+    vals, idx = bs.bs_prune_pack(Wd, wl.bank, wl.k)
+    del Wd
+    xd = torch.from_numpy(np.ascontiguousarray(X)).to(dev)
+    alg = wl.spmv_bytes()
+    R = rotation(alg)
+    copies = [(vals, idx)] + [(vals.clone(), idx.clone()) for _ in range(R - 1)]
+    y = torch.empty(wl.M, dtype=torch.float32, device=dev)
+    evict = Evictor(torch, probe, dev)
+    timer = GraphTimer(torch, probe, dev)
+    n = 400
+    code = bs.BS_F16 if wl.dtype == "f16" else bs.BS_F32
+
+    def timed(fn):
+        cap = timer.capture(fn, n, "sweep")
+        if cap is None:
+            return None
+        return round(min(timer.replay_us(cap, evict)[0] for _ in range(3)), 3)
+
+    out = {"workload": wl.name, "algorithmic_bytes": alg, "launches_per_graph": n, "copies": R,
+           "default": {"plan": bs.bs_spmv_plan(code, wl.M, wl.K, wl.bank, wl.k)}}
+    cs = [bs.PreparedSpmv(v, ix, wl.bank, xd, y) for v, ix in copies]
+    out["default"]["us"] = timed(lambda i: cs[i % R]())
+    print(f"default {out['default']}", file=sys.stderr, flush=True)
+    table = []
+    for lpr in (4, 8, 16, 32, 64):
+        for thr in (64, 128, 256, 384, 512, 768, 1024):
+            if thr % lpr:
+                continue
+            try:
+                plan = bs.bs_spmv_plan(code, wl.M, wl.K, wl.bank, wl.k, lpr, thr // lpr)
+            except bs.BsError:
+                continue
+            cs = [bs.PreparedSpmv(v, ix, wl.bank, xd, y, lpr, thr // lpr) for v, ix in copies]
+            us = timed(lambda i: cs[i % R]())
+            row = {"lanes_per_row": lpr, "rows_per_wg": thr // lpr, "threads": thr,
+                   "workgroups": plan["workgroups"], "chunk_slots": plan["u"], "us": us,
+                   "GBps": round(alg / us / 1e3, 1) if us else None}
+            table.append(row)
+            print(row, file=sys.stderr, flush=True)
+    out["shapes"] = table
+    # the floor for the same bytes, several shapes of the read-only kernel
+    same = (alg + 15) // 16 * 16
+    bufs = [torch.empty(same, dtype=torch.uint8, device=dev) for _ in range(R)]
+    for b_ in bufs:
+        b_.fill_(1)
+    out["read_only_us_by_pieces_per_lane"] = {
+        str(pc): timed(lambda i: probe.probe_stream_read(bufs[i % R], pc)) for pc in (1, 2, 4, 8)}
+    del bufs
+    out["empty_kernel_us"] = {f"{g}x{t}": timed(lambda i: probe.probe_empty(g, t))
+                              for g in (1, 64, 256, 750, 2207, 8828) for t in (64, 256, 1024)}
+    print(json.dumps(out))
+    return 0
 
 
 def main():
@@ -281,6 +399,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     bs.bs_init()
+    if args.sweep:
+        return sweep(args, torch, np, bs, probe, workloads, dev)
 
     wl, W, X = workloads.make(args.workload)
     K, W_steps = args.steps, args.warmup
@@ -290,7 +410,7 @@ def main():
     torch.cuda.synchronize()
 
     alg_bytes = wl.spmv_bytes()
-    R = 1 if args.warm else rotation(alg_bytes)
+    R = 1 if args.warm else max(rotation(alg_bytes), args.copies)
     copies = [(vals, idx)] + [(vals.clone(), idx.clone()) for _ in range(R - 1)]
     evict = None if args.warm else Evictor(torch, probe, dev)
     spmm = wl.N > 1
@@ -325,11 +445,16 @@ def main():
     # the first event, so the K launches start with empty caches and (rotating over R
     # copies) never come back to a copy before 2 x the last-level cache has gone by.
     mode = "eager"
-    graph = None if args.eager else capture(torch, step, K, "headline")
+    timer = GraphTimer(torch, probe, dev)
+    # pre-roll launches continue the rotation (copies K, K+1, ...), so with K < R they touch
+    # copies the timed launches do not
+    graph = None if args.eager else timer.capture(step, K, "headline")
+    replay_events_us = None
     t_wall0 = time.perf_counter()
     if graph is not None:
-        mode = "hip graph of K launches"
-        us_per_step = timed_replay_us(torch, graph, K, evict)
+        mode = (f"hip graph: {graph[2]} pre-roll launches, wall-clock stamp, the K launches, "
+                "wall-clock stamp")
+        us_per_step, replay_events_us = timer.replay_us(graph, evict)
     else:
         if evict is not None:
             evict()
@@ -338,9 +463,10 @@ def main():
     # the same region a few more times (extras): how far one sample of K steps can be off
     trials = []
     if graph is not None and not args.no_extras:
-        trials = [round(timed_replay_us(torch, graph, K, evict), 3) for _ in range(4)]
+        trials = [round(timer.replay_us(graph, evict)[0], 3) for _ in range(4)]
 
     value = alg_bytes / us_per_step / 1e3                  # GB/s
+    n_launched = K + (graph[2] if graph is not None else 0)
     touched = min(K, R) * alg_bytes
     if args.warm:
         residency = "warm (one copy, cache resident)"
@@ -362,8 +488,11 @@ def main():
                 "traffic": traffic,
                 "kernel": kernel_name,
                 "kernel_us": round(us_per_step, 3),
-                "how": "HIP events around the K launches of the timed region / K"
-                       + (" (main kernel + reduce kernel per step)" if spmm else "")}
+                "how": ("GPU wall-clock stamps (one-lane kernels inside the captured graph) right before "
+                        "and after the K launches, minus the interval of two adjacent stamps, / K"
+                        if graph is not None else "HIP events around K eager launches / K"),
+                "stamp_gap_us": round(timer.gap_us, 3),
+                "replay_events_us_per_launch": (round(replay_events_us, 3) if replay_events_us else None)}
 
     # ---- the machine's floor in the same protocol and the same run: an empty kernel of
     # the product's launch shape, and a kernel that only reads the product's algorithmic
@@ -374,22 +503,22 @@ def main():
             bufs = [torch.empty(same, dtype=torch.uint8, device=dev) for _ in range(R)]
             for b_ in bufs:
                 b_.fill_(1)
-            g_floor = capture(torch, lambda i: probe.probe_stream_read(bufs[i % R]), K, "floor: read-only kernel")
+            g_floor = timer.capture(lambda i: probe.probe_stream_read(bufs[i % R]), K, "floor: read-only kernel")
             if g_floor is not None:
-                floor_us = min(timed_replay_us(torch, g_floor, K, evict) for _ in range(3))
+                floor_us = min(timer.replay_us(g_floor, evict)[0] for _ in range(3))
                 roofline["floor_us"] = round(floor_us, 3)
                 roofline["floor_GBps"] = round(same / floor_us / 1e3, 1)
                 roofline["frac_of_floor"] = round(floor_us / us_per_step, 3)
                 roofline["floor"] = ("a kernel that only reads the same number of bytes (16 bytes per "
-                                     "lane, one piece per lane), same graph-of-K-launches protocol, "
-                                     "same eviction, rotating buffers; best of 3")
+                                     "lane, one piece per lane), same protocol (pre-roll, stamps, K "
+                                     "launches), same eviction, rotating buffers; best of 3")
             del bufs, g_floor
             grid, thr = (plan.get("workgroups") or 256), (plan.get("threads") or 256)
-            g_empty = capture(torch, lambda i: probe.probe_empty(int(grid), int(thr)), max(K, 200),
-                              "floor: empty kernel")
+            g_empty = timer.capture(lambda i: probe.probe_empty(int(grid), int(thr)), max(K, 200),
+                                    "floor: empty kernel")
             if g_empty is not None:
                 roofline["empty_launch_us"] = round(
-                    min(timed_replay_us(torch, g_empty, max(K, 200)) for _ in range(3)), 3)
+                    min(timer.replay_us(g_empty)[0] for _ in range(3)), 3)
             del g_empty
         except Exception as exc:                 # never lose the headline line
             roofline["floor_error"] = str(exc)[:200]
@@ -411,6 +540,7 @@ def main():
                                f"({100 * wl.sparsity:.3g}% sparse), batch {wl.N}",
                    "residency": residency,
                    "bytes_touched_by_timed_launches": touched,
+                   "launches_per_replay": n_launched,
                    "launch": mode,
                    "algorithmic_bytes_per_step": alg_bytes,
                    "flop_per_step": wl.flops()},
@@ -440,9 +570,9 @@ def main():
             extras["launch_floor_us"] = round(kernel_us_of(v1, i1, Xd, y1, wl.bank), 2)
             # the same matrix from cache (one copy): what an LSTM time step loop sees,
             # in the protocol of `value` (a graph of launches back to back)
-            gw = capture(torch, lambda i: bs.bs_spmv(vals, idx, wl.bank, Xd, out=Y), 64, "warm product")
+            gw = timer.capture(lambda i: bs.bs_spmv(vals, idx, wl.bank, Xd, out=Y), 64, "warm product")
             if gw is not None:
-                wg_us = min(timed_replay_us(torch, gw, 64) for _ in range(5))
+                wg_us = min(timer.replay_us(gw)[0] for _ in range(5))
                 extras["warm_us_per_launch_graph"] = round(wg_us, 3)
                 extras["warm_GBps_per_launch_graph"] = round(alg_bytes / wg_us / 1e3, 1)
             del gw
@@ -452,9 +582,9 @@ def main():
         Rd = 1 if args.warm else rotation(dense_bytes)
         Wc = [Wd] + [Wd.clone() for _ in range(Rd - 1)]
         if spmm:
-            d_us = graph_us(torch, lambda i: bs.bs_dense_gemm(Wc[i % Rd], Xd, out=Y), 20, "dense gemm", evict)
+            d_us = timer.us(lambda i: bs.bs_dense_gemm(Wc[i % Rd], Xd, out=Y), 20, "dense gemm", evict)
         else:
-            d_us = graph_us(torch, lambda i: bs.bs_dense_gemv(Wc[i % Rd], Xd, out=Y), 200, "dense gemv", evict)
+            d_us = timer.us(lambda i: bs.bs_dense_gemv(Wc[i % Rd], Xd, out=Y), 200, "dense gemv", evict)
         del Wc
         extras["dense_us"] = round(d_us, 2)
         extras["dense_GBps"] = round(dense_bytes / d_us / 1e3, 1)
@@ -464,7 +594,7 @@ def main():
         extras["ideal_us_eq5"] = round((d_us - o_time) * (1 - wl.sparsity) + o_time, 2)
         # one-time pruning + packing of the dense matrix
         p_out = (torch.empty_like(vals), torch.empty_like(idx))
-        p_us = graph_us(torch, lambda i: bs.bs_prune_pack(Wd, wl.bank, wl.k, out=p_out), 10, "prune_pack", evict)
+        p_us = timer.us(lambda i: bs.bs_prune_pack(Wd, wl.bank, wl.k, out=p_out), 10, "prune_pack", evict, preroll=2)
         p_bytes = W.nbytes + wl.nnz * (wl.val_bytes + 1)
         extras["prune_pack_us"] = round(p_us, 1)
         extras["prune_pack_GBps"] = round(p_bytes / p_us / 1e3, 1)
@@ -472,7 +602,7 @@ def main():
         if wl.k >= 2:
             k2 = wl.k // 2
             r_out = bs.bs_reprune(vals, idx, wl.bank, k2)
-            r_us = graph_us(torch, lambda i: bs.bs_reprune(vals, idx, wl.bank, k2, out=r_out), 20, "reprune")
+            r_us = timer.us(lambda i: bs.bs_reprune(vals, idx, wl.bank, k2, out=r_out), 20, "reprune", preroll=2)
             extras["reprune_to_half_us"] = round(r_us, 1)
             extras["reprune_GBps"] = round((wl.nnz + wl.M * (wl.K // wl.bank) * k2) *
                                            (wl.val_bytes + 1) / r_us / 1e3, 1)
@@ -486,21 +616,21 @@ def main():
             bufs = [torch.empty(big, dtype=torch.uint8, device=dev) for _ in range(3)]
             for b_ in bufs:
                 b_.fill_(1)
-            t_big = graph_us(torch, lambda i: probe.probe_stream_read(bufs[i % 3]), 12, "floor: 288 MB read")
+            t_big = timer.us(lambda i: probe.probe_stream_read(bufs[i % 3]), 12, "floor: 288 MB read", preroll=3)
             floor["stream_read_288MB_us"] = round(t_big, 2)
             floor["stream_read_288MB_GBps"] = round(big / t_big / 1e3, 1)
             del bufs
             # what an LDS gather costs: 256 workgroups of 768 lanes that only issue LDS reads;
             # ns per wavefront read and compute unit
             reads, thr = 16000, 768
-            t0 = graph_us(torch, lambda i: probe.probe_lds_gather(thr, 0, 16, 8), 4, "floor: lds fill")
+            t0 = timer.us(lambda i: probe.probe_lds_gather(thr, 0, 16, 8), 4, "floor: lds fill", preroll=1)
             lds = {}
             for key, pattern, lanes in (("b128_adjacent_1KB", 0, 16), ("b128_rows_of_256B", 1, 16),
                                         ("b128_rows_of_128B", 1, 8), ("b128_rows_of_64B", 1, 4),
                                         ("b128_rows_of_32B", 1, 2), ("b32_random_word_per_lane", 2, 16),
                                         ("b32_random_row_word_is_lane", 3, 16)):
-                t = graph_us(torch, lambda i: probe.probe_lds_gather(thr, pattern, lanes, reads), 4,
-                             "floor: lds gather")
+                t = timer.us(lambda i: probe.probe_lds_gather(thr, pattern, lanes, reads), 4,
+                             "floor: lds gather", preroll=1)
                 lds[key] = round((t - t0) * 1e3 / ((reads - 8) * thr / 64), 3)
             floor["lds_gather_ns_per_wavefront_read_per_cu"] = lds
             # grid barrier: workgroups -> us per round (256 lanes each, a 6 KB vector read and
@@ -532,10 +662,10 @@ def main():
                 Xs_h, h0_h, c0_h, b_h = workloads.draw_lstm_inputs(Hn, In, T, wl.seed)
                 Xs, h0, c0, bias = (torch.from_numpy(t).to(dev) for t in (Xs_h, h0_h, c0_h, b_h))
                 H_all = torch.empty((T, Hn), dtype=torch.float32, device=dev)
-                gl = capture(torch, lambda i: bs.bs_lstm_sequence(vals, idx, wl.bank, Xs, h0, bias, c0,
-                                                                  H_all=H_all), 1, "lstm sequence")
+                gl = timer.capture(lambda i: bs.bs_lstm_sequence(vals, idx, wl.bank, Xs, h0, bias, c0,
+                                                                 H_all=H_all), 1, "lstm sequence", preroll=1)
                 if gl is not None:
-                    l_us = min(timed_replay_us(torch, gl, T) for _ in range(5))
+                    l_us = min(timer.replay_us(gl)[0] for _ in range(5)) / T
                     extras["lstm_step_us_cache_resident"] = round(l_us, 3)
                     extras["lstm_steps_per_graph"] = T
                     extras["lstm_step_vs_dense_gemv_us"] = round(d_us, 2)
@@ -563,7 +693,7 @@ def main():
                 if name not in workloads.WORKLOADS:
                     continue
                 try:
-                    others[name] = quick_measure(torch, np, bs, workloads, dev, name, o_time, evict)
+                    others[name] = quick_measure(torch, np, bs, workloads, dev, name, o_time, evict, timer)
                 except Exception as exc:             # never lose the headline line
                     others[name] = {"error": str(exc)[:200]}
                 torch.cuda.empty_cache()

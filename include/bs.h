@@ -35,6 +35,10 @@
  *   - NaN or Inf inside W is undefined behaviour for bs_prune_pack.
  *   - Requires: bank in 1..256, K % bank == 0, 1 <= k <= bank, M >= 1,
  *     M*K < 2^40, K <= 2^24.
+ *   - Balance ranges over 256 (Sec. 3.1 leaves the range free; Sec. 4.1 uses 32 blocks
+ *     per row, which is more than 256 elements for any K > 8192) use the entry points
+ *     ending in _wide: the same layout with 16-bit offsets, bank up to
+ *     BS_WIDE_BANK_MAX.
  */
 #ifndef BS_H
 #define BS_H
@@ -164,7 +168,8 @@ int bs_spmv_plan(int dtype, int64_t M, int64_t K, int bank, int k, int lanes_per
  * Y   DEVICE out  M x N fp32 row-major, leading dimension ldy >= N
  * Y[r][n] = sum_j sum_t vals[r][j][t] * X[j*bank + idx[r][j][t]][n]
  * workspace / workspace_bytes: DEVICE scratch of at least
- * bs_spmm_workspace_bytes(...) bytes (may be NULL when that is 0).
+ * bs_spmm_workspace_bytes(...) bytes (may be NULL when that is 0), 16-byte aligned; it
+ * needs no initialisation.  Calls that overlap in time must not share a workspace.
  */
 size_t bs_spmm_workspace_bytes(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N);
 
@@ -187,6 +192,30 @@ int bs_spmm_plan(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N,
 int bs_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K,
             int bank, int k, const float* X, int64_t N, int64_t ldx,
             float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- balance ranges over 256: the same calls with 16-bit offsets -----------------
+ *
+ * Sec. 3.1 puts no bound on the balance range, and the default of Sec. 4.1 (32 blocks per
+ * row) exceeds 256 elements for any K > 8192.  The packed matrix has the same layout
+ * [M][K/bank][k]; idx holds uint16_t offsets (0 .. bank-1), strictly ascending inside a
+ * bank; ties keep the lower offset.  1 <= bank <= BS_WIDE_BANK_MAX; all other conventions
+ * and limits as above.
+ *   bs_prune_pack_wide  additionally needs bank * sizeof(element) to be a multiple of 16
+ *                       (bank % 4 == 0 for fp32, bank % 8 == 0 for binary16):
+ *                       BS_ERR_UNSUPPORTED otherwise.
+ *   bs_spmv_wide        K <= 40960 (x must fit LDS): BS_ERR_UNSUPPORTED beyond.
+ *   bs_spmm_wide        workspace of bs_spmm_workspace_bytes_wide(...) bytes, as for bs_spmm.
+ */
+#define BS_WIDE_BANK_MAX 2048
+size_t bs_idx_bytes_wide(int64_t M, int64_t K, int bank, int k);
+int bs_prune_pack_wide(const void* W, int dtype, int64_t M, int64_t K, int bank, int k,
+                       void* vals, uint16_t* idx, void* stream);
+int bs_spmv_wide(const void* vals, const uint16_t* idx, int dtype, int64_t M, int64_t K,
+                 int bank, int k, const float* x, float* y, void* stream);
+size_t bs_spmm_workspace_bytes_wide(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N);
+int bs_spmm_wide(const void* vals, const uint16_t* idx, int dtype, int64_t M, int64_t K,
+                 int bank, int k, const float* X, int64_t N, int64_t ldx,
+                 float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- one LSTM time step on a Balanced-Sparsity gate matrix (the recurrent
  *      models of Sec. 4.3: hidden size 1500 / 1024; eq. (1): W.X + B) --------

@@ -22,6 +22,7 @@ EXPORTS = (
     "bs_init", "bs_nnz", "bs_vals_bytes", "bs_idx_bytes", "bs_status_str", "bs_prune_pack", "bs_spmv",
     "bs_spmv_ex", "bs_spmv_plan", "bs_spmm_workspace_bytes", "bs_spmm_plan", "bs_spmm", "bs_dense_gemv", "bs_dense_gemm",
     "bs_lstm_step", "bs_lstm_sequence", "bs_reprune",
+    "bs_idx_bytes_wide", "bs_prune_pack_wide", "bs_spmv_wide", "bs_spmm_workspace_bytes_wide", "bs_spmm_wide",
 )
 
 
@@ -72,6 +73,15 @@ def load_library():
     lib.bs_reprune.argtypes = [vp, vp, i32, i64, i64, i32, i32, i32, vp, vp, vp]
     lib.bs_lstm_step.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.bs_lstm_sequence.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, vp, vp, vp, vp, vp]
+    lib.bs_idx_bytes_wide.argtypes = [i64, i64, i32, i32]
+    lib.bs_idx_bytes_wide.restype = sz
+    lib.bs_prune_pack_wide.argtypes = [vp, i32, i64, i64, i32, i32, vp, vp, vp]
+    lib.bs_spmv_wide.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, vp, vp]
+    lib.bs_spmm_workspace_bytes_wide.argtypes = [i32, i64, i64, i32, i32, i64]
+    lib.bs_spmm_workspace_bytes_wide.restype = sz
+    lib.bs_spmm_wide.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, i64, vp, i64, vp, sz, vp]
+    for name in ("bs_prune_pack_wide", "bs_spmv_wide", "bs_spmm_wide"):
+        getattr(lib, name).restype = i32
     lib.bs_init.argtypes = []
     for name in ("bs_init", "bs_prune_pack", "bs_spmv", "bs_spmv_ex", "bs_spmm", "bs_dense_gemv",
                  "bs_dense_gemm", "bs_lstm_step", "bs_lstm_sequence", "bs_reprune"):
@@ -242,8 +252,9 @@ def bs_spmv(vals, idx, bank: int, x, out=None, lanes_per_row: int = 0, rows_per_
 class PreparedSpmv:
     """bs_spmv_ex with its arguments marshalled once, for launch loops where the
     Python-side checks of :func:`bs_spmv` would dominate a microsecond kernel.
-    Each call is exactly one C-ABI call on the stream that was current at
-    construction; the tensors are kept alive by this object."""
+    Each call is exactly one C-ABI call on torch's current stream (read at every
+    call, so the same object works inside and outside a graph capture); the tensors
+    are kept alive by this object."""
 
     def __init__(self, vals, idx, bank: int, x, out, lanes_per_row: int = 0, rows_per_wg: int = 0):
         code, M, K, k = _packed(vals, idx, bank)
@@ -255,10 +266,9 @@ class PreparedSpmv:
         self._fn = load_library().bs_spmv_ex
         self._head = (_ptr(vals), _ptr(idx), code, M, K, bank, k, _ptr(x), _ptr(out),
                       lanes_per_row, rows_per_wg)
-        self._stream = _stream()
 
     def __call__(self, start_event: int = 0, stop_event: int = 0):
-        st = self._fn(*self._head, start_event, stop_event, self._stream)
+        st = self._fn(*self._head, start_event, stop_event, _stream())
         if st:
             raise BsError(st, "bs_spmv_ex")
 
@@ -267,6 +277,11 @@ def bs_spmv_ex(vals, idx, bank, x, lanes_per_row, rows_per_wg, out=None, start_e
                stop_event=0):
     return bs_spmv(vals, idx, bank, x, out=out, lanes_per_row=lanes_per_row,
                    rows_per_wg=rows_per_wg, start_event=start_event, stop_event=stop_event)
+
+
+def new_spmm_workspace(nbytes: int, device) -> torch.Tensor:
+    """A workspace for bs_spmm / bs_spmm_wide (uninitialised device memory)."""
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
 
 
 def bs_spmm(vals, idx, bank: int, X, out=None, workspace=None):
@@ -287,7 +302,7 @@ def bs_spmm(vals, idx, bank: int, X, out=None, workspace=None):
     lib = load_library()
     need = lib.bs_spmm_workspace_bytes(code, M, K, bank, k, N)
     if need and workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=vals.device)
+        workspace = new_spmm_workspace(need, vals.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.bs_spmm(_ptr(vals), _ptr(idx), code, M, K, bank, k, _ptr(X), N, ldx, _ptr(Y), ldy,
                        _ptr(workspace), ws_bytes, _stream()), "bs_spmm")
@@ -322,6 +337,86 @@ def bs_dense_gemm(W, X, out=None):
         out, "out", torch.float32)
     _check(load_library().bs_dense_gemm(_ptr(W), code, M, K, _ptr(X), N, N, _ptr(Y), N, _stream()),
            "bs_dense_gemm")
+    return Y
+
+
+# ---- balance ranges over 256: 16-bit offsets (torch has no uint16 arithmetic, but tensors of
+# that dtype can be allocated, copied and compared, which is all that is needed here)
+
+def bs_idx_bytes_wide(M: int, K: int, bank: int, k: int) -> int:
+    return load_library().bs_idx_bytes_wide(M, K, bank, k)
+
+
+def bs_spmm_workspace_bytes_wide(dtype: int, M: int, K: int, bank: int, k: int, N: int) -> int:
+    return load_library().bs_spmm_workspace_bytes_wide(dtype, M, K, bank, k, N)
+
+
+def bs_prune_pack_wide(W: torch.Tensor, bank: int, k: int, out=None):
+    """W [M, K] on the GPU (fp32/fp16) -> (vals [M, K/bank, k], idx uint16 same shape)."""
+    _dev(W, "W")
+    code = _dtype_code(W, "W")
+    if W.dim() != 2:
+        raise ValueError("W must be 2-D")
+    M, K = W.shape
+    if bank < 1 or K % bank or k < 1 or k > bank:
+        raise BsError(2, "bs_prune_pack_wide")
+    nb = K // bank
+    if out is None:
+        vals = torch.empty((M, nb, k), dtype=W.dtype, device=W.device)
+        idx = torch.empty((M, nb, k), dtype=torch.uint16, device=W.device)
+    else:
+        vals, idx = out
+        _dev(vals, "vals", W.dtype)
+        _dev(idx, "idx", torch.uint16)
+        if tuple(vals.shape) != (M, nb, k) or tuple(idx.shape) != (M, nb, k):
+            raise ValueError(f"out must be two [{M}, {nb}, {k}] tensors")
+    _check(load_library().bs_prune_pack_wide(_ptr(W), code, M, K, bank, k, _ptr(vals), _ptr(idx),
+                                             _stream()), "bs_prune_pack_wide")
+    return vals, idx
+
+
+def _packed_wide(vals, idx, bank):
+    _dev(vals, "vals")
+    _dev(idx, "idx", torch.uint16)
+    if vals.dim() != 3 or idx.shape != vals.shape:
+        raise ValueError("vals and idx must both be [M, K/bank, k]")
+    M, nb, k = vals.shape
+    return _dtype_code(vals, "vals"), M, nb * bank, k
+
+
+def bs_spmv_wide(vals, idx, bank: int, x, out=None):
+    """y [M] = W_sparse . x for a packed matrix with uint16 offsets."""
+    code, M, K, k = _packed_wide(vals, idx, bank)
+    _dev(x, "x", torch.float32)
+    if x.numel() != K:
+        raise ValueError(f"x must have {K} elements")
+    y = torch.empty(M, dtype=torch.float32, device=vals.device) if out is None else _dev(
+        out, "out", torch.float32)
+    if y.numel() != M:
+        raise ValueError(f"out must have {M} elements")
+    _check(load_library().bs_spmv_wide(_ptr(vals), _ptr(idx), code, M, K, bank, k, _ptr(x), _ptr(y),
+                                       _stream()), "bs_spmv_wide")
+    return y
+
+
+def bs_spmm_wide(vals, idx, bank: int, X, out=None, workspace=None):
+    """Y [M, N] = W_sparse . X for a packed matrix with uint16 offsets (see bs_spmm)."""
+    code, M, K, k = _packed_wide(vals, idx, bank)
+    ldx = _rows(X, "X")
+    if X.shape[0] != K:
+        raise ValueError(f"X must be [{K}, N]")
+    N = X.shape[1]
+    Y = torch.empty((M, N), dtype=torch.float32, device=vals.device) if out is None else out
+    ldy = _rows(Y, "out")
+    if tuple(Y.shape) != (M, N):
+        raise ValueError(f"out must be [{M}, {N}]")
+    lib = load_library()
+    need = lib.bs_spmm_workspace_bytes_wide(code, M, K, bank, k, N)
+    if need and workspace is None:
+        workspace = new_spmm_workspace(need, vals.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.bs_spmm_wide(_ptr(vals), _ptr(idx), code, M, K, bank, k, _ptr(X), N, ldx, _ptr(Y), ldy,
+                            _ptr(workspace), ws_bytes, _stream()), "bs_spmm_wide")
     return Y
 
 

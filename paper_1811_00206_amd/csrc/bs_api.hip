@@ -54,6 +54,11 @@ bool size_ok(int64_t M, int64_t K, int bank) {
     return bank <= 256 && K <= ((int64_t)1 << 24) && M <= ((int64_t)1 << 40) / K;
 }
 
+// the same for the entry points with 16-bit offsets
+bool size_ok_wide(int64_t M, int64_t K, int bank) {
+    return bank <= BS_WIDE_BANK_MAX && K <= ((int64_t)1 << 24) && M <= ((int64_t)1 << 40) / K;
+}
+
 bool dtype_ok(int dtype) { return dtype == BS_F32 || dtype == BS_F16; }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -63,6 +68,15 @@ int check_packed(const void* vals, const uint8_t* idx, int dtype, int64_t M, int
     if (!vals || !idx) return BS_ERR_NULL;
     if (!shape_ok(M, K, bank, k)) return BS_ERR_SHAPE;
     if (!dtype_ok(dtype) || !size_ok(M, K, bank)) return BS_ERR_UNSUPPORTED;
+    if (!aligned16(vals) || !aligned16(idx)) return BS_ERR_ALIGN;
+    return BS_OK;
+}
+
+int check_packed_wide(const void* vals, const uint16_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                      int k) {
+    if (!vals || !idx) return BS_ERR_NULL;
+    if (!shape_ok(M, K, bank, k)) return BS_ERR_SHAPE;
+    if (!dtype_ok(dtype) || !size_ok_wide(M, K, bank)) return BS_ERR_UNSUPPORTED;
     if (!aligned16(vals) || !aligned16(idx)) return BS_ERR_ALIGN;
     return BS_OK;
 }
@@ -108,6 +122,47 @@ int bs_prune_pack(const void* W, int dtype, int64_t M, int64_t K, int bank, int 
     if (!aligned16(W)) return BS_ERR_ALIGN;
     return bs::launch_prune_pack(W, dtype, M, K, bank, k, vals, idx,
                                  static_cast<hipStream_t>(stream));
+}
+
+size_t bs_idx_bytes_wide(int64_t M, int64_t K, int bank, int k) {
+    if (!shape_ok(M, K, bank, k) || !size_ok_wide(M, K, bank)) return 0;
+    return (size_t)M * (size_t)(K / bank) * (size_t)k * 2;
+}
+
+int bs_prune_pack_wide(const void* W, int dtype, int64_t M, int64_t K, int bank, int k, void* vals,
+                       uint16_t* idx, void* stream) {
+    if (!W) return BS_ERR_NULL;
+    int st = check_packed_wide(vals, idx, dtype, M, K, bank, k);
+    if (st) return st;
+    if (!aligned16(W)) return BS_ERR_ALIGN;
+    return bs::launch_prune_pack_wide(W, dtype, M, K, bank, k, vals, idx,
+                                      static_cast<hipStream_t>(stream));
+}
+
+int bs_spmv_wide(const void* vals, const uint16_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                 int k, const float* x, float* y, void* stream) {
+    if (!x || !y) return BS_ERR_NULL;
+    int st = check_packed_wide(vals, idx, dtype, M, K, bank, k);
+    if (st) return st;
+    if (!aligned16(x) || !aligned16(y)) return BS_ERR_ALIGN;
+    return bs::launch_spmv_wide(vals, idx, dtype, M, K, bank, k, x, y, static_cast<hipStream_t>(stream));
+}
+
+size_t bs_spmm_workspace_bytes_wide(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N) {
+    if (!shape_ok(M, K, bank, k) || !dtype_ok(dtype) || !size_ok_wide(M, K, bank) || N < 1) return 0;
+    return bs::spmm_workspace_bytes_wide(dtype, M, K, bank, k, N);
+}
+
+int bs_spmm_wide(const void* vals, const uint16_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                 int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
+                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (!X || !Y) return BS_ERR_NULL;
+    int st = check_packed_wide(vals, idx, dtype, M, K, bank, k);
+    if (st) return st;
+    if (N < 1 || ldx < N || ldy < N) return BS_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(Y)) return BS_ERR_ALIGN;
+    return bs::launch_spmm_wide(vals, idx, dtype, M, K, bank, k, X, N, ldx, Y, ldy, workspace,
+                                workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 int bs_reprune(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,

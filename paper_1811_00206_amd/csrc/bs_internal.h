@@ -20,6 +20,15 @@ constexpr int kMaxLdsBytes = 160 * 1024;   // LDS of one gfx950 compute unit
 // Launchers (host).  Arguments are already validated by the C-ABI layer.
 int launch_prune_pack(const void* W, int dtype, int64_t M, int64_t K, int bank, int k,
                       void* vals, uint8_t* idx, hipStream_t st);
+// 16-bit offsets (balance ranges over 256)
+int launch_prune_pack_wide(const void* W, int dtype, int64_t M, int64_t K, int bank, int k,
+                           void* vals, uint16_t* idx, hipStream_t st);
+int launch_spmv_wide(const void* vals, const uint16_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                     int k, const float* x, float* y, hipStream_t st);
+size_t spmm_workspace_bytes_wide(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N);
+int launch_spmm_wide(const void* vals, const uint16_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                     int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
+                     void* workspace, size_t workspace_bytes, hipStream_t st);
 int launch_reprune(const void* vals, const uint8_t* idx, int dtype, int64_t n_banks, int k, int k2,
                    void* vals2, uint8_t* idx2, hipStream_t st);
 int launch_spmv(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
@@ -141,12 +150,25 @@ __device__ __forceinline__ int group_sum_i(int v) {
 template <int W>
 __device__ __forceinline__ int group_prefix_i(int v, int q) {
     int incl = v;
+    // inclusive sums inside each row of 16 lanes (a row shift never crosses a row) ...
     if constexpr (W >= 2) { int t = dpp_move_i<0x111>(incl); if (q >= 1) incl += t; }   // row_shr:1
     if constexpr (W >= 4) { int t = dpp_move_i<0x112>(incl); if (q >= 2) incl += t; }   // row_shr:2
     if constexpr (W >= 8) { int t = dpp_move_i<0x114>(incl); if (q >= 4) incl += t; }   // row_shr:4
     if constexpr (W >= 16) { int t = dpp_move_i<0x118>(incl); if (q >= 8) incl += t; }  // row_shr:8
-    if constexpr (W >= 32) { int t = __shfl_up(incl, 16, 64); if (q >= 16) incl += t; }
-    if constexpr (W >= 64) { int t = __shfl_up(incl, 32, 64); if (q >= 32) incl += t; }
+    // ... then the totals of the group's earlier rows (held by each row's last lane), all
+    // fetched before any is added
+    if constexpr (W >= 32) {
+        const int first = (int)(threadIdx.x & (kWave - 1)) - q;   // first lane of the group
+        const int t0 = __shfl(incl, first + 15, kWave);
+        int t1 = 0, t2 = 0;
+        if constexpr (W >= 64) {
+            t1 = __shfl(incl, first + 31, kWave);
+            t2 = __shfl(incl, first + 47, kWave);
+        }
+        if (q >= 16) incl += t0;
+        if (q >= 32) incl += t1;
+        if (q >= 48) incl += t2;
+    }
     return incl - v;
 }
 
@@ -192,6 +214,35 @@ __device__ __forceinline__ float value_at(const RAW& raw, int i) {
 template <typename RAW>
 __device__ __forceinline__ uint32_t offset_at(const RAW& raw, int i) {
     return (word_of(raw, i >> 2) >> ((i & 3) * 8)) & 0xffu;
+}
+
+// A chunk of 16-bit offsets (balance ranges over 256): the same raw bytes, read two per word.
+template <typename RAW>
+struct WideIdx {
+    RAW r;
+};
+template <typename RAW>
+__device__ __forceinline__ uint32_t word_of(const WideIdx<RAW>& w, int i) { return word_of(w.r, i); }
+template <typename RAW>
+__device__ __forceinline__ uint32_t offset_at(const WideIdx<RAW>& w, int i) {
+    return (word_of(w.r, i >> 1) >> ((i & 1) * 16)) & 0xffffu;
+}
+
+// IT = uint8_t or uint16_t: the raw type of a chunk of CH stored offsets
+template <typename IT, int CH>
+struct IdxChunk {
+    using type = typename RawBytes<CH>::type;
+};
+template <int CH>
+struct IdxChunk<uint16_t, CH> {
+    using type = WideIdx<typename RawBytes<2 * CH>::type>;
+};
+
+// offset i of a chunk whose 32-bit words are held in ow[] (IB = bytes per offset)
+template <int IB>
+__device__ __forceinline__ uint32_t offset_from_words(const uint32_t* ow, int i) {
+    if constexpr (IB == 1) return (ow[i >> 2] >> ((i & 3) * 8)) & 0xffu;
+    else return (ow[i >> 1] >> ((i & 1) * 16)) & 0xffffu;
 }
 
 template <typename T>

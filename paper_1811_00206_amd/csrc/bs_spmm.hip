@@ -29,7 +29,9 @@ int64_t gcd64(int64_t a, int64_t b) { while (b) { int64_t t = a % b; a = b; b = 
 
 // One candidate: tiles of `quads` groups of 4 columns (a power of two).  Cost = bytes moved through L2 (tiles of
 // X staged by every workgroup, W once per column tile, slab partial sums twice).
-SpmmPlan plan_for(int quads, int dtype, int64_t M, int64_t K, int bank, int k, int64_t N) {
+// isize: bytes per stored offset; with 2 the kernels exist for the widest chunk and for
+// single entries only.
+SpmmPlan plan_for(int quads, int dtype, int64_t M, int64_t K, int bank, int k, int64_t N, int isize) {
     SpmmPlan p{};
     // one float4 per lane and entry: the lanes of a column group then read one
     // contiguous piece of an LDS row, which costs the fewest bank conflicts
@@ -56,6 +58,7 @@ SpmmPlan plan_for(int quads, int dtype, int64_t M, int64_t K, int bank, int k, i
     while (sb > 1 && sb * per_bank + (size_t)sb * k * 4 > (size_t)kMaxLdsBytes) --sb;
     if (sb * per_bank + (size_t)sb * k * 4 > (size_t)kMaxLdsBytes) return p;
     if (sb < nb) while (ch > 1 && (sb * k) % ch != 0) ch >>= 1;
+    if (isize == 2 && ch != 16 / vsize) ch = 1;
 
     p.ch = ch;
     p.q = q;
@@ -113,14 +116,14 @@ SpmmPlan plan_for(int quads, int dtype, int64_t M, int64_t K, int bank, int k, i
     if (threads > max_threads) threads = max_threads;
     p.threads = (int)threads;
     p.ws_bytes = p.n_slabs > 1 ? (size_t)p.n_slabs * M * N * 4 : 0;
-    const double w_bytes = (double)M * row_len * (vsize + 1);
+    const double w_bytes = (double)M * row_len * (vsize + isize);
     p.cost = (double)p.row_groups * p.n_tiles * p.n_slabs * tile_bytes + p.n_tiles * w_bytes +
              2.0 * p.ws_bytes;
     p.ok = true;
     return p;
 }
 
-SpmmPlan make_plan(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N) {
+SpmmPlan make_plan(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N, int isize = 1) {
     SpmmPlan best{};
     // Tiles of at most 32 columns: with 64 the LDS rows are 256 bytes, half as many banks of
     // X fit a slab and a wavefront holds 4 rows instead of 8; measured on ten shapes the
@@ -128,7 +131,7 @@ SpmmPlan make_plan(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N) 
     // 17.8 us; 1024 x 1024 at N = 512: 15.9 against 13.0 us).
     for (int quads = 1; quads <= 8; quads <<= 1) {
         if (quads > 1 && 4 * (quads / 2) >= N) break;   // the narrower tile already covers N
-        SpmmPlan p = plan_for(quads, dtype, M, K, bank, k, N);
+        SpmmPlan p = plan_for(quads, dtype, M, K, bank, k, N, isize);
         if (p.ok && (!best.ok || p.cost < best.cost)) best = p;
     }
     return best;
@@ -193,11 +196,12 @@ int spmm_plan_describe(int dtype, int64_t M, int64_t K, int bank, int k, int64_t
     return BS_OK;
 }
 
-int launch_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
-                int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
-                void* workspace, size_t workspace_bytes, hipStream_t st) {
+namespace {
+int launch_spmm_any(const void* vals, const void* idx, int isize, int dtype, int64_t M, int64_t K, int bank,
+                    int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
+                    void* workspace, size_t workspace_bytes, hipStream_t st) {
     if (M > INT32_MAX / 4 || N > INT32_MAX / 4) return BS_ERR_UNSUPPORTED;
-    const SpmmPlan p = make_plan(dtype, M, K, bank, k, N);
+    const SpmmPlan p = make_plan(dtype, M, K, bank, k, N, isize);
     if (!p.ok || p.lds_bytes > (size_t)kMaxLdsBytes) return BS_ERR_UNSUPPORTED;
     if (p.ws_bytes) {
         if (M * N > (int64_t)UINT32_MAX) return BS_ERR_UNSUPPORTED;   // the reduce kernel's 32-bit rows
@@ -229,7 +233,8 @@ int launch_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int6
     a.vec_out = (a.ld_out % 4 == 0 && a.slab_stride % 4 == 0 && (uintptr_t)a.out % 16 == 0) ? 1 : 0;
 
     const SpmmLaunch l{p.threads, p.lds_bytes, st};
-    int st_code = p.rows ? spmm_rows_launch(dtype, p.ch, a, l)
+    int st_code = isize == 2 ? spmm_launch_wide(dtype, p.rows, p.ch, p.lpr, p.u, a, l)
+                  : p.rows ? spmm_rows_launch(dtype, p.ch, a, l)
                   : dtype == BS_F16 ? spmm_launch_f16(p.ch, p.lpr, p.u, p.q, a, l)
                                     : spmm_launch_f32(p.ch, p.lpr, p.u, p.q, a, l);
     if (st_code != BS_OK) return st_code;
@@ -247,6 +252,26 @@ int launch_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int6
         return hip_status(hipGetLastError());
     }
     return BS_OK;
+}
+}  // namespace
+
+int launch_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
+                void* workspace, size_t workspace_bytes, hipStream_t st) {
+    return launch_spmm_any(vals, idx, 1, dtype, M, K, bank, k, X, N, ldx, Y, ldy, workspace,
+                           workspace_bytes, st);
+}
+
+int launch_spmm_wide(const void* vals, const uint16_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                     int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
+                     void* workspace, size_t workspace_bytes, hipStream_t st) {
+    return launch_spmm_any(vals, idx, 2, dtype, M, K, bank, k, X, N, ldx, Y, ldy, workspace,
+                           workspace_bytes, st);
+}
+
+size_t spmm_workspace_bytes_wide(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N) {
+    const SpmmPlan p = make_plan(dtype, M, K, bank, k, N, 2);
+    return p.ok ? p.ws_bytes : 0;
 }
 
 }  // namespace bs

@@ -24,7 +24,10 @@
 //     (two register sets: one receives loads, the other is a copy);
 //   * the LPR partial sums (nl lanes apart) are combined with lane exchanges; with more than one slab
 //     the slab results go to a workspace and a second kernel adds them in slab
-//     order, so results do not depend on scheduling;
+//     order, so results do not depend on scheduling (adding them in the workgroup that
+//     finishes last for a tile and row group, behind an agent-scope counter, was measured
+//     2-3 us slower per product than the second launch: the L2 write-back and invalidate
+//     around the counter and the last arriver's reads from the other XCDs cost more);
 //   * workgroups that share a tile get consecutive numbers after an XCD-aware
 //     remap, so the tile of X is fetched into one XCD's L2.
 #pragma once
@@ -38,7 +41,7 @@ constexpr int kXcds = 8;
 
 struct SpmmArgs {
     const void* vals;
-    const uint8_t* idx;
+    const void* idx;       // uint8_t, or uint16_t in the kernels for balance ranges over 256
     const float* X;
     float* out;            // Y (one slab) or the workspace [n_slabs][M][N]
     int64_t ldx;
@@ -68,6 +71,8 @@ struct SpmmLaunch {
 
 int spmm_launch_f32(int ch, int lpr, int u, int q, const SpmmArgs& a, const SpmmLaunch& l);
 int spmm_launch_f16(int ch, int lpr, int u, int q, const SpmmArgs& a, const SpmmLaunch& l);
+// 16-bit offsets (bs_spmm_wide.hip): both kernels, ch the widest chunk or 1
+int spmm_launch_wide(int dtype, bool rows, int ch, int lpr, int u, const SpmmArgs& a, const SpmmLaunch& l);
 
 #ifdef __HIPCC__
 
@@ -203,12 +208,12 @@ __device__ __forceinline__ void spmm_consume(const char* xcol, const uint32_t* t
     if (live == 1) return spmm_slots<VT, CH, LPR, U, Q, 1>(xcol, tab, pitch, v, o, c0, ragged, cps, acc);
 }
 
-template <typename VT, int CH, int LPR, int U, int Q>
+template <typename VT, int CH, int LPR, int U, int Q, typename IT = uint8_t>
 __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
     static_assert(Q == 1, "one group of four columns per lane");
     extern __shared__ __align__(16) float Xs[];
     using VRaw = typename RawBytes<CH * sizeof(VT)>::type;
-    using IRaw = typename RawBytes<CH>::type;
+    using IRaw = typename IdxChunk<IT, CH>::type;
 
     int z, s, g;
     if (!spmm_which_tile(a, z, s, g)) return;
@@ -257,7 +262,7 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
         const int rc = min(r_first + pass * rows_per_pass, r_end - 1);
         const size_t e0 = ((size_t)rc * a.nb + j0) * a.k;
         ld_v = reinterpret_cast<const VRaw*>(vbase + e0);
-        ld_i = reinterpret_cast<const IRaw*>(a.idx + e0);
+        ld_i = reinterpret_cast<const IRaw*>(static_cast<const IT*>(a.idx) + e0);
     };
     auto issue = [&]() {
 #pragma unroll
@@ -327,9 +332,9 @@ __global__ __launch_bounds__(1024) void spmm_kernel(SpmmArgs a) {
     }
 }
 
-template <typename VT, int CH, int LPR, int U, int Q>
+template <typename VT, int CH, int LPR, int U, int Q, typename IT = uint8_t>
 int spmm_launch_one(const SpmmArgs& a, const SpmmLaunch& l) {
-    constexpr auto kern = spmm_kernel<VT, CH, LPR, U, Q>;
+    constexpr auto kern = spmm_kernel<VT, CH, LPR, U, Q, IT>;
     if (l.lds > 48 * 1024) {
         const int st_code = ensure_lds_limit(LdsKernelOf<kern>::reg, l.st);
         if (st_code != BS_OK) return st_code;

@@ -48,7 +48,8 @@ __device__ __forceinline__ void spmm_rows_operands(const char* xcol, const uint3
                                                    uint32_t pitch_shift, const VRaw& v, const IRaw& o,
                                                    const char** row, float* w) {
     constexpr int VW = CH * (int)sizeof(VT) / 4 > 0 ? CH * (int)sizeof(VT) / 4 : 1;   // words of values
-    constexpr int IW = (CH + 3) / 4;                                                   // words of offsets
+    constexpr int IB = (int)sizeof(IRaw) / CH;                                         // bytes per offset
+    constexpr int IW = (CH * IB + 3) / 4;                                              // words of offsets
     uint32_t vw[VW], ow[IW];
 #pragma unroll
     for (int i = 0; i < VW; ++i) vw[i] = quad_lane<QQ>(word_of(v, i));
@@ -72,7 +73,7 @@ __device__ __forceinline__ void spmm_rows_operands(const char* xcol, const uint3
     }
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
-        const uint32_t off = (ow[i >> 2] >> ((i & 3) * 8)) & 0xffu;
+        const uint32_t off = offset_from_words<IB>(ow, i);
         row[i] = xcol + base[i] + (off << pitch_shift);
         if constexpr (sizeof(VT) == 4) {
             w[i] = __builtin_bit_cast(float, vw[i]);
@@ -117,11 +118,11 @@ __device__ __forceinline__ void spmm_rows_chunks(const char* xcol, const uint32_
     spmm_rows_fma<NC * CH>(row, w, acc);
 }
 
-template <typename VT, int CH, int UC>
+template <typename VT, int CH, int UC, typename IT = uint8_t>
 __global__ __launch_bounds__(1024) void spmm_rows_kernel(SpmmArgs a) {
     extern __shared__ __align__(16) float Xs[];
     using VRaw = typename RawBytes<CH * sizeof(VT)>::type;
-    using IRaw = typename RawBytes<CH>::type;
+    using IRaw = typename IdxChunk<IT, CH>::type;
 
     int z, s, g;
     if (!spmm_which_tile(a, z, s, g)) return;
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(1024) void spmm_rows_kernel(SpmmArgs a) {
         const int rc = min(r_first + pass * rows_per_pass, r_end - 1);
         const size_t e0 = ((size_t)rc * a.nb + j0) * a.k;
         ld_v = reinterpret_cast<const VRaw*>(vbase + e0);
-        ld_i = reinterpret_cast<const IRaw*>(a.idx + e0);
+        ld_i = reinterpret_cast<const IRaw*>(static_cast<const IT*>(a.idx) + e0);
     };
     auto issue = [&](VRaw (&v)[UC], IRaw (&o)[UC]) {
 #pragma unroll
@@ -255,9 +256,9 @@ __global__ __launch_bounds__(1024) void spmm_rows_kernel(SpmmArgs a) {
     }
 }
 
-template <typename VT, int CH>
+template <typename VT, int CH, typename IT = uint8_t>
 int spmm_rows_launch_one(const SpmmArgs& a, const SpmmLaunch& l) {
-    constexpr auto kern = spmm_rows_kernel<VT, CH, 4>;
+    constexpr auto kern = spmm_rows_kernel<VT, CH, 4, IT>;
     if (l.lds > 48 * 1024) {
         const int st_code = ensure_lds_limit(LdsKernelOf<kern>::reg, l.st);
         if (st_code != BS_OK) return st_code;

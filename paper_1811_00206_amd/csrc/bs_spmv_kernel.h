@@ -30,7 +30,7 @@ namespace bs {
 
 struct SpmvArgs {
     const void* vals;
-    const uint8_t* idx;
+    const void* idx;        // uint8_t, or uint16_t in the kernels for balance ranges over 256
     const float* x;
     float* y;
     int M;
@@ -71,6 +71,8 @@ struct SpmvLaunch {
 // launchers instantiated per storage type (one translation unit each)
 int spmv_launch_f32(int ch, int lpr, int u, const SpmvArgs& a, const SpmvLaunch& l);
 int spmv_launch_f16(int ch, int lpr, int u, const SpmvArgs& a, const SpmvLaunch& l);
+// 16-bit offsets (bs_spmv_wide.hip): ch is the widest chunk or 1, lpr 8..64, u 2, 4 or 8
+int spmv_launch_wide(int dtype, int ch, int lpr, int u, const SpmvArgs& a, const SpmvLaunch& l);
 
 #ifdef __HIPCC__
 
@@ -201,11 +203,12 @@ __device__ __forceinline__ float tanh_fast(float v) {
 // LSTM: the rows are the four gate pre-activations of hidden units and the kernel
 // ends with the cell update (the model of Sec. 4.3; bias as in eq. (1)) instead of
 // storing y: a workgroup owns rows_per_wg/4 units, its row i is gate i%4 of unit i/4.
-template <typename VT, int CH, int LPR, int U, bool LSTM = false>
+// IT: the stored offset type (uint8_t, or uint16_t for balance ranges over 256).
+template <typename VT, int CH, int LPR, int U, bool LSTM = false, typename IT = uint8_t>
 __global__ __launch_bounds__(1024) void spmv_kernel(SpmvArgs a) {
     extern __shared__ __align__(16) float xs[];
     using VRaw = typename RawBytes<CH * sizeof(VT)>::type;
-    using IRaw = typename RawBytes<CH>::type;
+    using IRaw = typename IdxChunk<IT, CH>::type;
     const int tid = threadIdx.x;
     const int nthr = blockDim.x;
     const int lane_in_row = tid % LPR;
@@ -243,7 +246,7 @@ __global__ __launch_bounds__(1024) void spmv_kernel(SpmvArgs a) {
 
     const VRaw* vrow = reinterpret_cast<const VRaw*>(
         static_cast<const VT*>(a.vals) + (size_t)rowc * a.row_len);
-    const IRaw* irow = reinterpret_cast<const IRaw*>(a.idx + (size_t)rowc * a.row_len);
+    const IRaw* irow = reinterpret_cast<const IRaw*>(static_cast<const IT*>(a.idx) + (size_t)rowc * a.row_len);
     const int cpr = a.chunks_per_row;
 
     // (1) x -> LDS with direct-to-LDS loads: each wavefront copies 1 KB pieces
@@ -348,9 +351,9 @@ __global__ __launch_bounds__(1024) void spmv_kernel(SpmvArgs a) {
     }
 }
 
-template <typename VT, int CH, int LPR, int U, bool LSTM = false>
+template <typename VT, int CH, int LPR, int U, bool LSTM = false, typename IT = uint8_t>
 int spmv_launch_one(const SpmvArgs& a, const SpmvLaunch& l) {
-    constexpr auto kern = spmv_kernel<VT, CH, LPR, U, LSTM>;
+    constexpr auto kern = spmv_kernel<VT, CH, LPR, U, LSTM, IT>;
     if (l.lds > 48 * 1024) {
         const int st_code = ensure_lds_limit(LdsKernelOf<kern>::reg, l.st);
         if (st_code != BS_OK) return st_code;

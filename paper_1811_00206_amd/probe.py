@@ -14,7 +14,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libbs_probe.so")
 
-EXPORTS = ("bs_probe_empty", "bs_probe_stream_read", "bs_probe_lds_gather", "bs_probe_grid_barrier")
+EXPORTS = ("bs_probe_timestamp", "bs_probe_wall_clock_khz", "bs_probe_empty", "bs_probe_stream_read", "bs_probe_lds_gather", "bs_probe_grid_barrier")
 
 _lib = None
 
@@ -38,6 +38,8 @@ def load_library():
             f"{_LIB_PATH} is missing: build it with `python -m paper_1811_00206_amd.build`")
     lib = ctypes.CDLL(_LIB_PATH)
     i32, u32, vp, sz = ctypes.c_int, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_size_t
+    lib.bs_probe_timestamp.argtypes = [vp, vp]
+    lib.bs_probe_wall_clock_khz.argtypes = []
     lib.bs_probe_empty.argtypes = [i32, i32, vp]
     lib.bs_probe_stream_read.argtypes = [vp, sz, i32, vp, vp]
     lib.bs_probe_lds_gather.argtypes = [i32, i32, i32, i32, vp, vp]
@@ -65,6 +67,19 @@ def _dev(t, what):
     if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous():
         raise TypeError(f"{what} must be a contiguous tensor on the GPU")
     return t
+
+
+def probe_timestamp(slots: torch.Tensor, i: int):
+    """Store the GPU's wall clock into slots[i] (an int64 tensor on the GPU) on the current stream."""
+    _dev(slots, "slots")
+    if slots.dtype != torch.int64 or not 0 <= i < slots.numel():
+        raise ValueError("slots must be an int64 tensor and i inside it")
+    _check(load_library().bs_probe_timestamp(ctypes.c_void_p(slots.data_ptr() + 8 * i), _stream()),
+           "bs_probe_timestamp")
+
+
+def wall_clock_khz() -> int:
+    return load_library().bs_probe_wall_clock_khz()
 
 
 def probe_empty(grid: int = 256, threads: int = 256):

@@ -27,6 +27,13 @@ extern "C" {
  * multiple of 64). */
 int bs_probe_empty(int grid, int threads, void* stream);
 
+/* A one-lane kernel that stores the GPU's constant-rate wall clock into DEVICE `slot`
+ * (8-byte aligned).  Two of them around a run of launches inside one captured graph time
+ * that run on the GPU itself, free of what launching the graph costs.
+ * bs_probe_wall_clock_khz: the clock's rate on the current device (0 if unknown). */
+int bs_probe_timestamp(uint64_t* slot, void* stream);
+int bs_probe_wall_clock_khz(void);
+
 /* A kernel that only reads `bytes` bytes (a multiple of 16, at least 16) from DEVICE
  * `src`, 16 bytes per lane and load, and stores nothing.  `sink` is DEVICE memory of at
  * least 256 bytes that is never written for real data (may be NULL).

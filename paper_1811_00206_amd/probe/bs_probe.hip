@@ -22,6 +22,11 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 __global__ void probe_empty_kernel() {}
 
+// one lane stores the constant-rate wall clock (its rate: hipDeviceAttributeWallClockRate)
+__global__ void probe_timestamp_kernel(unsigned long long* slot) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *slot = wall_clock64();
+}
+
 // every lane reads 16-byte pieces, U in flight; the sum is stored only if it has a
 // value the data cannot produce, so the loads cannot be dropped
 template <int U>
@@ -168,6 +173,21 @@ int bs_probe_empty(int grid, int threads, void* stream) {
     if (grid < 1 || grid > 65536 || threads < 64 || threads > 1024 || threads % 64) return kErrShape;
     hipLaunchKernelGGL(probe_empty_kernel, dim3(grid), dim3(threads), 0, static_cast<hipStream_t>(stream));
     return hip_status(hipGetLastError());
+}
+
+int bs_probe_timestamp(uint64_t* slot, void* stream) {
+    if (!slot) return kErrNull;
+    if (reinterpret_cast<uintptr_t>(slot) & 7u) return kErrAlign;
+    hipLaunchKernelGGL(probe_timestamp_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream),
+                       reinterpret_cast<unsigned long long*>(slot));
+    return hip_status(hipGetLastError());
+}
+
+int bs_probe_wall_clock_khz(void) {
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess) return 0;
+    return khz;
 }
 
 int bs_probe_stream_read(const void* src, size_t bytes, int pieces_per_lane, void* sink, void* stream) {

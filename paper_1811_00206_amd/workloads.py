@@ -50,10 +50,15 @@ class Workload:
     def val_bytes(self) -> int:
         return 4 if self.dtype == "f32" else 2
 
+    @property
+    def idx_bytes(self) -> int:
+        """Bytes per stored offset: one, or two for balance ranges over 256."""
+        return 1 if self.bank <= 256 else 2
+
     def spmv_bytes(self) -> int:
         """Algorithmic HBM bytes of one sparse product: every stored value and
         offset once, X once, Y once."""
-        return self.nnz * (self.val_bytes + 1) + 4 * self.K * self.N + 4 * self.M * self.N
+        return self.nnz * (self.val_bytes + self.idx_bytes) + 4 * self.K * self.N + 4 * self.M * self.N
 
     def dense_bytes(self) -> int:
         return self.M * self.K * self.val_bytes + 4 * self.K * self.N + 4 * self.M * self.N
@@ -104,6 +109,10 @@ WORKLOADS = {w.name: w for w in [
     _mk(8, "lstm1500_b100_k20", 6000, 3000, 100, 20, 0.05),
     # Sec. 4.3's second recurrent model: hidden size 1024 (input size taken as 1024), 87.5 %
     _mk(7, "bilstm1024", 4096, 2048, 64, 8, 0.05),
+    # balance ranges over 256 (16-bit offsets): Sec. 4.1's matrix with 16 and 8 banks per row
+    _mk(10, "bench16k_b512_k64", 16384, 8192, 512, 64, 1.0),
+    _mk(10, "bench16k_b1024_k128", 16384, 8192, 1024, 128, 1.0),
+    _mk(10, "bench16k_b512_k64_n8", 16384, 8192, 512, 64, 1.0, N=8),
     _mk(6, "bench16k_k128_n8", 16384, 8192, 256, 128, 1.0, N=8),
     _mk(6, "bench16k_k32_n8", 16384, 8192, 256, 32, 1.0, N=8),
     _mk(6, "bench16k_k8_n8", 16384, 8192, 256, 8, 1.0, N=8),

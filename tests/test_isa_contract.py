@@ -20,7 +20,7 @@ import pytest
 from paper_1811_00206_amd import build as bs_build
 
 SOURCES = ["bs_spmv_f32.hip", "bs_spmv_f16.hip", "bs_spmm_f32.hip", "bs_spmm_f16.hip",
-           "bs_spmm_rows.hip", "bs_spmv_slab.hip"]
+           "bs_spmm_rows.hip", "bs_spmv_slab.hip", "bs_spmv_wide.hip", "bs_spmm_wide.hip"]
 
 
 def _assembly(src):
@@ -79,10 +79,12 @@ def test_every_instantiation_is_present(kernels):
     # 3 chunk widths for fp32 + 4 for fp16, 7 group widths; 7 in-flight depths for
     # SpMV, plus 4 group widths and 2 depths of the fused LSTM step; 5 group widths
     # and 2 depths for SpMM
-    assert sum("spmv_kernel" in n for n in kernels) == (3 + 4) * 7 * 7 + (3 + 4) * 4 * 2
-    assert sum("spmm_kernel" in n for n in kernels) == (3 + 4) * 5 * 2
+    # ... and for 16-bit offsets: 2 chunk widths per type, 4 group widths, 3 depths for SpMV;
+    # 2 chunk widths, 5 group widths, 2 depths for SpMM
+    assert sum("spmv_kernel" in n for n in kernels) == (3 + 4) * 7 * 7 + (3 + 4) * 4 * 2 + 2 * 2 * 4 * 3
+    assert sum("spmm_kernel" in n for n in kernels) == (3 + 4) * 5 * 2 + 2 * 2 * 5 * 2
     # one lane per (row, column group): chunk widths only
-    assert sum("spmm_rows_kernel" in n for n in kernels) == 3 + 4
+    assert sum("spmm_rows_kernel" in n for n in kernels) == 3 + 4 + 2 * 2
 
 
 def test_wait_before_barrier_covers_the_copy_of_x(kernels):
