@@ -58,7 +58,8 @@ typedef enum {
     BS_ERR_ALIGN = 4,       /* a base pointer is not 16-byte aligned              */
     BS_ERR_HIP = 5,         /* the HIP runtime refused the launch                 */
     BS_ERR_WORKSPACE = 6,   /* workspace missing or smaller than required         */
-    BS_ERR_NOT_INITIALISED = 7 /* first use of a kernel inside a stream capture     */
+    BS_ERR_NOT_INITIALISED = 7, /* first use of a kernel inside a stream capture    */
+    BS_ERR_SCRATCH_LIMIT = 8 /* bs_spmm_static: needs more than the static scratch   */
 } bs_status;
 
 /* storage type of W and vals; x, X, y, Y and all accumulation are fp32 */
@@ -192,6 +193,28 @@ int bs_spmm_plan(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N,
 int bs_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K,
             int bank, int k, const float* X, int64_t N, int64_t ldx,
             float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * bs_spmm for callers that cannot allocate device memory or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and bit-identical results as bs_spmm, but the slab partial
+ * sums go to a static device array inside the library (bs_spmm_static_limit() bytes,
+ * 16 MiB, held on every GPU the library runs on until the process ends) instead of a
+ * caller workspace.  The call allocates and frees nothing.
+ *   - A product whose bs_spmm_workspace_bytes(...) exceeds the limit returns
+ *     BS_ERR_SCRATCH_LIMIT and enqueues nothing.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one
+ *     GPU (different streams, several threads) race on it.  Calls on one stream, or
+ *     otherwise ordered, are fine; nothing in the array needs to survive between calls
+ *     (every partial sum that is read was written by the same call).
+ *   - The array's address is looked up once per device, in bs_init() or at the first
+ *     call on that device; like every first use this never happens inside a capture
+ *     (BS_ERR_NOT_INITIALISED then).
+ */
+size_t bs_spmm_static_limit(void);
+int bs_spmm_static(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K,
+                   int bank, int k, const float* X, int64_t N, int64_t ldx,
+                   float* Y, int64_t ldy, void* stream);
 
 /* ---- balance ranges over 256: the same calls with 16-bit offsets -----------------
  *

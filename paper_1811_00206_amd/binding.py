@@ -20,7 +20,7 @@ BS_F32, BS_F16 = 0, 1
 
 EXPORTS = (
     "bs_init", "bs_nnz", "bs_vals_bytes", "bs_idx_bytes", "bs_status_str", "bs_prune_pack", "bs_spmv",
-    "bs_spmv_ex", "bs_spmv_plan", "bs_spmm_workspace_bytes", "bs_spmm_plan", "bs_spmm", "bs_dense_gemv", "bs_dense_gemm",
+    "bs_spmv_ex", "bs_spmv_plan", "bs_spmm_workspace_bytes", "bs_spmm_plan", "bs_spmm", "bs_spmm_static", "bs_spmm_static_limit", "bs_dense_gemv", "bs_dense_gemm",
     "bs_lstm_step", "bs_lstm_sequence", "bs_reprune",
     "bs_idx_bytes_wide", "bs_prune_pack_wide", "bs_spmv_wide", "bs_spmm_workspace_bytes_wide", "bs_spmm_wide",
 )
@@ -68,6 +68,9 @@ def load_library():
     lib.bs_spmm_plan.argtypes = [i32, i64, i64, i32, i32, i64, ctypes.POINTER(ctypes.c_int64), i32]
     lib.bs_spmm_plan.restype = i32
     lib.bs_spmm.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, i64, vp, i64, vp, sz, vp]
+    lib.bs_spmm_static.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i64, i64, vp, i64, vp]
+    lib.bs_spmm_static_limit.argtypes = []
+    lib.bs_spmm_static_limit.restype = sz
     lib.bs_dense_gemv.argtypes = [vp, i32, i64, i64, vp, vp, vp]
     lib.bs_dense_gemm.argtypes = [vp, i32, i64, i64, vp, i64, i64, vp, i64, vp]
     lib.bs_reprune.argtypes = [vp, vp, i32, i64, i64, i32, i32, i32, vp, vp, vp]
@@ -83,7 +86,7 @@ def load_library():
     for name in ("bs_prune_pack_wide", "bs_spmv_wide", "bs_spmm_wide"):
         getattr(lib, name).restype = i32
     lib.bs_init.argtypes = []
-    for name in ("bs_init", "bs_prune_pack", "bs_spmv", "bs_spmv_ex", "bs_spmm", "bs_dense_gemv",
+    for name in ("bs_init", "bs_prune_pack", "bs_spmv", "bs_spmv_ex", "bs_spmm", "bs_spmm_static", "bs_dense_gemv",
                  "bs_dense_gemm", "bs_lstm_step", "bs_lstm_sequence", "bs_reprune"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -307,6 +310,27 @@ def bs_spmm(vals, idx, bank: int, X, out=None, workspace=None):
     _check(lib.bs_spmm(_ptr(vals), _ptr(idx), code, M, K, bank, k, _ptr(X), N, ldx, _ptr(Y), ldy,
                        _ptr(workspace), ws_bytes, _stream()), "bs_spmm")
     return Y
+
+
+def bs_spmm_static_limit() -> int:
+    return load_library().bs_spmm_static_limit()
+
+
+def bs_spmm_static(vals, idx, bank: int, X, out):
+    """bs_spmm without a workspace and without any allocation: the slab partial sums go to
+    the library's static device array, and `out` must be given (this wrapper allocates
+    nothing either).  Calls that overlap on one GPU race on that array."""
+    code, M, K, k = _packed(vals, idx, bank)
+    ldx = _rows(X, "X")
+    if X.shape[0] != K:
+        raise ValueError(f"X must be [{K}, N]")
+    N = X.shape[1]
+    ldy = _rows(out, "out")
+    if tuple(out.shape) != (M, N):
+        raise ValueError(f"out must be [{M}, {N}]")
+    _check(load_library().bs_spmm_static(_ptr(vals), _ptr(idx), code, M, K, bank, k, _ptr(X), N, ldx,
+                                         _ptr(out), ldy, _stream()), "bs_spmm_static")
+    return out
 
 
 def bs_dense_gemv(W, x, out=None):

@@ -38,7 +38,7 @@ int init_current_device() {
         const int st = raise_on_current_device(*k, bit);
         if (st != BS_OK) return st;
     }
-    return BS_OK;
+    return static_scratch_lookup();
 }
 
 }  // namespace bs
@@ -108,6 +108,8 @@ const char* bs_status_str(int status) {
         case BS_ERR_ALIGN: return "pointer not 16-byte aligned";
         case BS_ERR_HIP: return "HIP runtime error";
         case BS_ERR_WORKSPACE: return "workspace missing or too small";
+        case BS_ERR_SCRATCH_LIMIT:
+            return "the product needs more scratch than the library's static buffer holds";
         case BS_ERR_NOT_INITIALISED:
             return "first use of a kernel inside a stream capture: call bs_init() on this device first";
     }
@@ -259,6 +261,19 @@ int bs_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t 
     if (!aligned16(X) || !aligned16(Y)) return BS_ERR_ALIGN;
     return bs::launch_spmm(vals, idx, dtype, M, K, bank, k, X, N, ldx, Y, ldy, workspace,
                            workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+size_t bs_spmm_static_limit(void) { return bs::kStaticScratchBytes; }
+
+int bs_spmm_static(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                   int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy, void* stream) {
+    if (!X || !Y) return BS_ERR_NULL;
+    int st = check_packed(vals, idx, dtype, M, K, bank, k);
+    if (st) return st;
+    if (N < 1 || ldx < N || ldy < N) return BS_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(Y)) return BS_ERR_ALIGN;
+    return bs::launch_spmm_static(vals, idx, dtype, M, K, bank, k, X, N, ldx, Y, ldy,
+                                  static_cast<hipStream_t>(stream));
 }
 
 int bs_dense_gemv(const void* W, int dtype, int64_t M, int64_t K, const float* x, float* y,

@@ -50,6 +50,12 @@ int spmm_plan_describe(int dtype, int64_t M, int64_t K, int bank, int k, int64_t
 int launch_spmm(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
                 int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
                 void* workspace, size_t workspace_bytes, hipStream_t st);
+// bs_spmm_static: the slab partial sums in a file-scope device array of this many bytes
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+int static_scratch_lookup();   // finds the array's address on the current device (bs_init)
+int launch_spmm_static(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K,
+                       int bank, int k, const float* X, int64_t N, int64_t ldx, float* Y,
+                       int64_t ldy, hipStream_t st);
 int launch_dense_gemv(const void* W, int dtype, int64_t M, int64_t K, const float* x, float* y,
                       hipStream_t st);
 int launch_dense_gemm(const void* W, int dtype, int64_t M, int64_t K, const float* X, int64_t N,

@@ -172,7 +172,46 @@ __global__ __launch_bounds__(256) void spmm_reduce_kernel(const float* __restric
     }
 }
 
+// ---- scratch for callers that cannot allocate (bs_spmm_static) -------------------
+// The slab partial sums of such a call live in this array.  In host code the array's
+// name is only a stand-in: the address kernels and copies may use is what
+// hipGetSymbolAddress reports, once per device, with that device current.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::atomic<void*> g_scratch_ptr[64];
+
 }  // namespace
+
+int static_scratch_lookup() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) return BS_ERR_HIP;
+    if (g_scratch_ptr[dev].load(std::memory_order_acquire)) return BS_OK;
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return BS_ERR_HIP;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    return BS_OK;
+}
+
+int launch_spmm_static(const void* vals, const uint8_t* idx, int dtype, int64_t M, int64_t K, int bank,
+                       int k, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
+                       hipStream_t st) {
+    if (M > INT32_MAX / 4 || N > INT32_MAX / 4) return BS_ERR_UNSUPPORTED;
+    const SpmmPlan p = make_plan(dtype, M, K, bank, k, N);
+    if (!p.ok) return BS_ERR_UNSUPPORTED;
+    if (p.ws_bytes > kStaticScratchBytes) return BS_ERR_SCRATCH_LIMIT;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) return BS_ERR_HIP;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        // first call on this device: look the address up, but never inside a capture
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(st, &cs) != hipSuccess) return BS_ERR_HIP;
+        if (cs != hipStreamCaptureStatusNone) return BS_ERR_NOT_INITIALISED;
+        const int rc = static_scratch_lookup();
+        if (rc != BS_OK) return rc;
+        ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    }
+    return launch_spmm(vals, idx, dtype, M, K, bank, k, X, N, ldx, Y, ldy, ptr, kStaticScratchBytes, st);
+}
 
 size_t spmm_workspace_bytes(int dtype, int64_t M, int64_t K, int bank, int k, int64_t N) {
     const SpmmPlan p = make_plan(dtype, M, K, bank, k, N);

@@ -86,6 +86,14 @@ def test_bad_arguments_are_refused_before_launch():
     assert lib.bs_lstm_step(p, p, 0, 6, 8, 2, 1, p, p, p, p, p, p, null) == 3       # H % 4
     assert lib.bs_lstm_step(p, p, 0, 8, 8, 2, 1, p, p, p, p, p, p, null) == 3       # h_out == h_in
     assert lib.bs_reprune(p, p, 0, 4, 8, 4, 2, 3, p, p, null) == 2                  # k2 > k
+    # the no-allocation product validates like bs_spmm, and refuses a product over its static
+    # scratch before it touches the GPU
+    assert lib.bs_spmm_static(p, p, 0, 4, 8, 4, 2, p, 4, 3, p, 4, null) == 2         # ldx < N
+    assert lib.bs_spmm_static(p, null, 0, 4, 8, 4, 2, p, 4, 4, p, 4, null) == 1
+    assert b.bs_spmm_workspace_bytes(b.BS_F32, 6000, 3000, 100, 10, 2048) > b.bs_spmm_static_limit()
+    assert lib.bs_spmm_static(p, p, 0, 6000, 3000, 100, 10, p, 2048, 2048, p, 2048, null) == 8
+    assert "scratch" in b.bs_status_str(8)
+    assert b.bs_spmm_static_limit() == 16 << 20
 
 
 def test_first_use_inside_a_capture_has_its_own_status():
