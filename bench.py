@@ -512,6 +512,19 @@ def main():
                 roofline["floor"] = ("a kernel that only reads the same number of bytes (16 bytes per "
                                      "lane, one piece per lane), same protocol (pre-roll, stamps, K "
                                      "launches), same eviction, rotating buffers; best of 3")
+                # ... and the same kernel when it also stores as many words as the product has
+                # results (one lane in every few stores its sum to consecutive words)
+                n_out = wl.M * wl.N
+                every = max(1, (same // 16) // n_out)
+                sink = torch.zeros((same // 16 + 256) // every + 2, dtype=torch.int32, device=dev)
+                g_fs = timer.capture(lambda i: probe.probe_stream_read(bufs[i % R], 1, sink=sink, store_mode=1,
+                                                                       store_every=every),
+                                     K, "floor: read-and-store kernel")
+                if g_fs is not None:
+                    fs_us = min(timer.replay_us(g_fs, evict)[0] for _ in range(3))
+                    roofline["floor_with_result_stores_us"] = round(fs_us, 3)
+                    roofline["frac_of_floor_with_result_stores"] = round(fs_us / us_per_step, 3)
+                del g_fs, sink
             del bufs, g_floor
             grid, thr = (plan.get("workgroups") or 256), (plan.get("threads") or 256)
             g_empty = timer.capture(lambda i: probe.probe_empty(int(grid), int(thr)), max(K, 200),

@@ -41,7 +41,7 @@ def load_library():
     lib.bs_probe_timestamp.argtypes = [vp, vp]
     lib.bs_probe_wall_clock_khz.argtypes = []
     lib.bs_probe_empty.argtypes = [i32, i32, vp]
-    lib.bs_probe_stream_read.argtypes = [vp, sz, i32, vp, vp]
+    lib.bs_probe_stream_read.argtypes = [vp, sz, i32, i32, i32, vp, sz, vp]
     lib.bs_probe_lds_gather.argtypes = [i32, i32, i32, i32, vp, vp]
     lib.bs_probe_grid_barrier.argtypes = [i32, i32, i32, i32, i32, u32, vp, vp, vp]
     for name in EXPORTS:
@@ -87,12 +87,16 @@ def probe_empty(grid: int = 256, threads: int = 256):
     _check(load_library().bs_probe_empty(grid, threads, _stream()), "bs_probe_empty")
 
 
-def probe_stream_read(src: torch.Tensor, pieces_per_lane: int = 0, sink: torch.Tensor = None):
-    """A kernel that only reads all of `src` (bytes a multiple of 16)."""
+def probe_stream_read(src: torch.Tensor, pieces_per_lane: int = 0, sink: torch.Tensor = None,
+                      store_mode: int = 0, store_every: int = 32):
+    """A kernel that only reads all of `src` (bytes a multiple of 16); with store_mode 1..3 one
+    lane in `store_every` also stores a word to `sink` (plain / non-temporal / agent-scope
+    atomic store)."""
     _dev(src, "src")
     nbytes = src.numel() * src.element_size()
-    _check(load_library().bs_probe_stream_read(_ptr(src), nbytes, pieces_per_lane, _ptr(sink), _stream()),
-           "bs_probe_stream_read")
+    sink_bytes = 0 if sink is None else sink.numel() * sink.element_size()
+    _check(load_library().bs_probe_stream_read(_ptr(src), nbytes, pieces_per_lane, store_mode, store_every,
+                                               _ptr(sink), sink_bytes, _stream()), "bs_probe_stream_read")
 
 
 def probe_lds_gather(threads: int = 768, pattern: int = 1, group_lanes: int = 8, reads: int = 16000):

@@ -35,13 +35,18 @@ int bs_probe_timestamp(uint64_t* slot, void* stream);
 int bs_probe_wall_clock_khz(void);
 
 /* A kernel that only reads `bytes` bytes (a multiple of 16, at least 16) from DEVICE
- * `src`, 16 bytes per lane and load, and stores nothing.  `sink` is DEVICE memory of at
- * least 256 bytes that is never written for real data (may be NULL).
+ * `src`, 16 bytes per lane and load.
  * pieces_per_lane: 0 = the fastest known shape for the size (one piece per lane and as
  * many short-lived workgroups as needed up to 64 MB, 8 pieces in flight per lane on a
- * fixed grid above); 1, 2, 4 or 8 = that many pieces per lane. */
-int bs_probe_stream_read(const void* src, size_t bytes, int pieces_per_lane, void* sink,
-                         void* stream);
+ * fixed grid above); 1, 2, 4 or 8 = that many pieces per lane.
+ * store_mode: 0 = nothing is stored (`sink`, DEVICE memory of at least 256 bytes or NULL, is
+ * never written for real data); 1, 2, 3 = one lane in `store_every` (>= 1) stores 4 bytes
+ * to consecutive words of `sink` (what a matrix-vector product does with its row sums)
+ * with a plain store, a non-temporal store, or an agent-scope atomic store; `sink_bytes`
+ * must then cover one word per `store_every` lanes launched (bytes / (16 * pieces_per_lane)
+ * lanes, rounded up to whole workgroups of 256) plus one. */
+int bs_probe_stream_read(const void* src, size_t bytes, int pieces_per_lane, int store_mode,
+                         int store_every, void* sink, size_t sink_bytes, void* stream);
 
 /* 256 workgroups of `threads` lanes (64..1024, a multiple of 64) fill 120 KB of LDS and
  * then issue `reads` (a multiple of 8) 16-byte LDS reads per lane and nothing else.

@@ -29,10 +29,13 @@ __global__ void probe_timestamp_kernel(unsigned long long* slot) {
 
 // every lane reads 16-byte pieces, U in flight; the sum is stored only if it has a
 // value the data cannot produce, so the loads cannot be dropped
-template <int U>
+// STORE: 0 = nothing is stored; otherwise one lane in `every` stores its sum to consecutive
+// words (what a matrix-vector product does with its row sums): 1 = a plain store, 2 = a
+// non-temporal store, 3 = an agent-scope atomic store (written through the L2 cache).
+template <int U, int STORE>
 __global__ __launch_bounds__(256) void probe_stream_read_kernel(const uint4* __restrict__ src,
                                                                 uint32_t* __restrict__ sink,
-                                                                size_t n16) {
+                                                                size_t n16, uint32_t every) {
     const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t nthr = (size_t)gridDim.x * blockDim.x;
     uint32_t acc = 0;
@@ -46,7 +49,14 @@ __global__ __launch_bounds__(256) void probe_stream_read_kernel(const uint4* __r
 #pragma unroll
         for (int u = 0; u < U; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
-    if (acc == 0x9e3779b9u && sink) sink[tid & 63] = acc;
+    if constexpr (STORE == 0) {
+        if (acc == 0x9e3779b9u && sink) sink[tid & 63] = acc;
+    } else if (tid % every == 0) {
+        uint32_t* dst = sink + tid / every;
+        if constexpr (STORE == 1) *dst = acc;
+        else if constexpr (STORE == 2) __builtin_nontemporal_store(acc, dst);
+        else __hip_atomic_store(dst, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 // LDS gather rate: every lane holds 8 fixed LDS addresses and reads from each, again and
@@ -190,12 +200,14 @@ int bs_probe_wall_clock_khz(void) {
     return khz;
 }
 
-int bs_probe_stream_read(const void* src, size_t bytes, int pieces_per_lane, void* sink, void* stream) {
+int bs_probe_stream_read(const void* src, size_t bytes, int pieces_per_lane, int store_mode,
+                         int store_every, void* sink, size_t sink_bytes, void* stream) {
     if (!src) return kErrNull;
     if (bytes < 16 || bytes % 16) return kErrShape;
     if (pieces_per_lane != 0 && pieces_per_lane != 1 && pieces_per_lane != 2 && pieces_per_lane != 4 &&
         pieces_per_lane != 8)
         return kErrShape;
+    if (store_mode < 0 || store_mode > 3 || (store_mode && store_every < 1)) return kErrShape;
     if (!aligned16(src) || (sink && !aligned16(sink))) return kErrAlign;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t n16 = bytes / 16;
@@ -208,12 +220,28 @@ int bs_probe_stream_read(const void* src, size_t bytes, int pieces_per_lane, voi
     if (u == 0) u = n16 <= (size_t)16384 * 256 ? 1 : 8;
     size_t grid = (n16 + 256 * (size_t)u - 1) / (256 * (size_t)u);
     if (grid > 65536) grid = 65536;
-    switch (u) {
-        case 1: hipLaunchKernelGGL(probe_stream_read_kernel<1>, dim3((unsigned)grid), dim3(256), 0, st, p, s, n16); break;
-        case 2: hipLaunchKernelGGL(probe_stream_read_kernel<2>, dim3((unsigned)grid), dim3(256), 0, st, p, s, n16); break;
-        case 4: hipLaunchKernelGGL(probe_stream_read_kernel<4>, dim3((unsigned)grid), dim3(256), 0, st, p, s, n16); break;
-        default: hipLaunchKernelGGL(probe_stream_read_kernel<8>, dim3((unsigned)grid), dim3(256), 0, st, p, s, n16); break;
+    if (store_mode) {   // one 4-byte store per `store_every` lanes launched
+        if (!sink) return kErrNull;
+        if (sink_bytes < (grid * 256 / (size_t)store_every + 1) * 4) return kErrShape;
+    } else if (sink && sink_bytes < 256) {
+        return kErrShape;
     }
+    const dim3 g((unsigned)grid), b(256);
+    const uint32_t every = store_mode ? (uint32_t)store_every : 1u;
+#define BS_PROBE_READ(UU)                                                                            \
+    switch (store_mode) {                                                                            \
+        case 0: hipLaunchKernelGGL((probe_stream_read_kernel<UU, 0>), g, b, 0, st, p, s, n16, every); break; \
+        case 1: hipLaunchKernelGGL((probe_stream_read_kernel<UU, 1>), g, b, 0, st, p, s, n16, every); break; \
+        case 2: hipLaunchKernelGGL((probe_stream_read_kernel<UU, 2>), g, b, 0, st, p, s, n16, every); break; \
+        default: hipLaunchKernelGGL((probe_stream_read_kernel<UU, 3>), g, b, 0, st, p, s, n16, every); break; \
+    }
+    switch (u) {
+        case 1: BS_PROBE_READ(1) break;
+        case 2: BS_PROBE_READ(2) break;
+        case 4: BS_PROBE_READ(4) break;
+        default: BS_PROBE_READ(8) break;
+    }
+#undef BS_PROBE_READ
     return hip_status(hipGetLastError());
 }
 

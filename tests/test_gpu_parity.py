@@ -510,6 +510,10 @@ def test_measurement_helpers_run_and_refuse_bad_sizes():
     for pieces in (1, 2, 4, 8):
         probe.probe_stream_read(buf, pieces)
     probe.probe_stream_read(buf[:4096], sink=torch.zeros(64, dtype=torch.int32, device=DEV))
+    sink = torch.zeros((1 << 20) // 128 + 1, dtype=torch.int32, device=DEV)
+    for mode in (1, 2, 3):
+        probe.probe_stream_read(buf, 1, sink=sink, store_mode=mode, store_every=8)
+        probe.probe_stream_read(buf, 1, sink=sink, store_mode=mode, store_every=94)
     torch.cuda.synchronize()
     assert bool((buf == 1).all())
     with pytest.raises(probe.ProbeError):

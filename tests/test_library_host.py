@@ -111,8 +111,10 @@ def test_probe_library_is_separate():
         assert getattr(plib, n) is not None
     null = ctypes.c_void_p(0)
     assert plib.bs_probe_empty(0, 256, null) == 2
-    assert plib.bs_probe_stream_read(null, 64, 0, null, null) == 1
-    assert plib.bs_probe_stream_read(ctypes.c_void_p(4096), 24, 0, null, null) == 2
+    assert plib.bs_probe_stream_read(null, 64, 0, 0, 0, null, 0, null) == 1
+    assert plib.bs_probe_stream_read(ctypes.c_void_p(4096), 24, 0, 0, 0, null, 0, null) == 2
+    assert plib.bs_probe_stream_read(ctypes.c_void_p(4096), 4096, 1, 1, 32, ctypes.c_void_p(8192), 16, null) == 2
+    assert plib.bs_probe_stream_read(ctypes.c_void_p(4096), 4096, 1, 1, 0, ctypes.c_void_p(8192), 4096, null) == 2
     assert plib.bs_probe_lds_gather(768, 1, 3, 64, null, null) == 2
     assert plib.bs_probe_grid_barrier(257, 256, 10, 1500, 0, 100, ctypes.c_void_p(4096),
                                       ctypes.c_void_p(4096), null) == 2
