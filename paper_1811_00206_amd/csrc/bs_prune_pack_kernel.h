@@ -109,9 +109,11 @@ __global__ __launch_bounds__(256) void prune_pack_lanes(const VT* __restrict__ W
     const int64_t n_groups = (n_banks + BPW - 1) / BPW;
     const int pieces = B / E;
 
-    // per wavefront: BPW*k value slots, then BPW*k offsets (each rounded up to whole words)
+    // per wavefront: BPW*k value slots and one trash slot per lane, then as many offsets (each
+    // rounded up to whole words)
     extern __shared__ uint32_t pp_lds[];
-    const int words_v = (BPW * k * (int)sizeof(VT) + 3) / 4, words_i = (BPW * k * (int)sizeof(IT) + 3) / 4;
+    const int words_v = ((BPW * k + kWave) * (int)sizeof(VT) + 3) / 4,
+              words_i = ((BPW * k + kWave) * (int)sizeof(IT) + 3) / 4;
     U* lds_v = reinterpret_cast<U*>(pp_lds + (threadIdx.x / kWave) * (words_v + words_i));
     IT* lds_i = reinterpret_cast<IT*>(reinterpret_cast<uint32_t*>(lds_v) + words_v);
 
@@ -221,22 +223,60 @@ __global__ __launch_bounds__(256) void prune_pack_lanes(const VT* __restrict__ W
         // Output slots in offset order: pieces ascend with j, then with the lane.  The
         // wavefront's banks are adjacent in vals and idx, so the kept entries are put in
         // order in the wavefront's own LDS and leave as whole words.
-        int kept_base = (lane / LPB) * k;
+        // The kept counts of a lane's R pieces are packed FPW to a word, so one prefix and one
+        // sum over the group's lanes serve FPW pieces (a field holds a whole group's count).
+        constexpr int FB = LPB * E < 256 ? 8 : 16, FPW = 32 / FB, NW = (R + FPW - 1) / FPW;
+        uint32_t pms[R], packed[NW];
+#pragma unroll
+        for (int w = 0; w < NW; ++w) packed[w] = 0u;
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            const uint32_t pm = (keep[(j * E) / 32] >> ((j * E) % 32)) & ((1u << E) - 1u);
-            const int ck = __popc(pm);
-            int slot = kept_base + group_prefix_i<LPB>(ck, q);
-            kept_base += group_sum_i<LPB>(ck);
-            const int off0 = (q + LPB * j) * E;
+            pms[j] = (keep[(j * E) / 32] >> ((j * E) % 32)) & ((1u << E) - 1u);
+            packed[j / FPW] |= (uint32_t)__popc(pms[j]) << ((j % FPW) * FB);
+        }
+        uint32_t before[NW], total[NW];
 #pragma unroll
-            for (int i = 0; i < E; ++i) {
-                if (pm & (1u << i)) {
+        for (int w = 0; w < NW; ++w) {
+            before[w] = (uint32_t)group_prefix_i<LPB>((int)packed[w], q);
+            total[w] = (uint32_t)group_sum_i<LPB>((int)packed[w]);
+        }
+        int kept_base = (lane / LPB) * k;
+        const int trash = BPW * k + lane;   // a slot of the lane's own behind the wavefront's output
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            constexpr uint32_t kField = (1u << FB) - 1u;
+            const uint32_t pm = pms[j];
+            const int slot = kept_base + (int)((before[j / FPW] >> ((j % FPW) * FB)) & kField);
+            kept_base += (int)((total[j / FPW] >> ((j % FPW) * FB)) & kField);
+            const int off0 = (q + LPB * j) * E;
+            // Pieces of four elements are written without branches (every element is stored,
+            // a dropped one to the lane's trash slot: 5-8 % faster on the fp32 matrices);
+            // with 8 binary16 elements or single elements per piece most stores would be
+            // wasted and the conditional form is faster (measured both ways).
+            constexpr bool kBranchFree = E == 4;
+            if (remap || !kBranchFree) {   // remap: re-pruning, the survivors carry the stored offsets
+                int at = slot;
+#pragma unroll
+                for (int i = 0; i < E; ++i) {
+                    if (pm & (1u << i)) {
+                        uint32_t v = word_of(raw[j], sizeof(VT) == 4 ? i : i >> 1);
+                        if (sizeof(VT) == 2) v = (i & 1) ? (v >> 16) : (v & 0xffffu);
+                        lds_v[at] = (U)v;
+                        lds_i[at] = remap ? remap[g * B + off0 + i] : (IT)(off0 + i);
+                        ++at;
+                    }
+                }
+            } else {
+                int n_before = 0;
+#pragma unroll
+                for (int i = 0; i < E; ++i) {
+                    const int kept = (int)((pm >> i) & 1u);
+                    const int at = kept ? slot + n_before : trash;
                     uint32_t v = word_of(raw[j], sizeof(VT) == 4 ? i : i >> 1);
                     if (sizeof(VT) == 2) v = (i & 1) ? (v >> 16) : (v & 0xffffu);
-                    lds_v[slot] = (U)v;
-                    lds_i[slot] = remap ? remap[g * B + off0 + i] : (IT)(off0 + i);
-                    ++slot;
+                    lds_v[at] = (U)v;
+                    lds_i[at] = (IT)(off0 + i);
+                    n_before += kept;
                 }
             }
         }
@@ -281,8 +321,9 @@ int launch_shape(const VT* w, VT* v, IT* idx, const IT* remap, int64_t n_banks, 
         const int64_t cap = 256 * 16;
         if (grid > cap) grid = cap;
         constexpr int BPW = kWave / LPB;
+        const size_t slots = (size_t)BPW * k + kWave;   // the wavefront's output and a trash slot per lane
         const size_t lds = (size_t)(threads / kWave) * 4 *
-                           (((size_t)BPW * k * sizeof(VT) + 3) / 4 + ((size_t)BPW * k * sizeof(IT) + 3) / 4);
+                           ((slots * sizeof(VT) + 3) / 4 + (slots * sizeof(IT) + 3) / 4);
         hipLaunchKernelGGL((prune_pack_lanes<VT, IT, PB, LPB, R>), dim3((unsigned)grid), dim3(threads),
                            lds, st, w, v, idx, remap, n_banks, bank, k);
         return hip_status(hipGetLastError());
