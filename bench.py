@@ -48,7 +48,8 @@ EVICT_BYTES = 768 << 20
 # belongs to one kernel instantiation; it is reported only while bs_spmv_plan still names
 # that instantiation for the workload.
 MEASURED_TRAFFIC = {
-    ("lstm1500", "cold"): {"kernel": "spmv_kernel<float,4,32,3>", "bytes": 9_252_196},
+    # FETCH_SIZE 4494.0 KiB x 1.9932 (the copy kernels' calibration) + WRITE_SIZE 23.4 KiB
+    ("lstm1500", "cold"): {"kernel": "spmv_kernel<float,4,32,3> 250 x 768", "bytes": 9_196_322},
 }
 
 
@@ -314,7 +315,7 @@ def spmv_kernel_name(bs, wl):
     if p["slab_kernel"]:
         return "spmv_slab_kernel", p
     vt = "__half" if wl.dtype == "f16" else "float"
-    return f"spmv_kernel<{vt},{p['ch']},{p['lpr']},{p['u']}>", p
+    return f"spmv_kernel<{vt},{p['ch']},{p['lpr']},{p['u']}> {p['workgroups']} x {p['threads']}", p
 
 
 def sweep(args, torch, np, bs, probe, workloads, dev):
@@ -633,6 +634,31 @@ def main():
             floor["stream_read_288MB_us"] = round(t_big, 2)
             floor["stream_read_288MB_GBps"] = round(big / t_big / 1e3, 1)
             del bufs
+            # what storing costs a kernel of this size: the read-only kernel of the product's bytes
+            # with different store patterns (cold, the protocol of `value`)
+            same = (alg_bytes + 15) // 16 * 16
+            if not args.warm and same // 16 <= 16384 * 256:
+                Rf = rotation(same)
+                bufs = [torch.empty(same, dtype=torch.uint8, device=dev) for _ in range(Rf)]
+                for b_ in bufs:
+                    b_.fill_(1)
+                sink = torch.zeros(((same // 16 + 255) // 256 + 1) * 32, dtype=torch.int32, device=dev)
+                n_out = wl.M * wl.N
+                every = max(1, (same // 16) // n_out)
+                stores = {}
+                for key, mode, ev_ in (("no_store", 0, 1),
+                                       (f"one_word_per_{every}_lanes_plain_store", 1, every),
+                                       (f"one_word_per_{every}_lanes_nontemporal_store", 2, every),
+                                       (f"one_word_per_{every}_lanes_agent_scope_store", 3, every),
+                                       ("one_word_per_32_lanes_plain_store", 1, 32),
+                                       ("one_instruction_per_workgroup_32_adjacent_words", 4, 32),
+                                       ("one_instruction_per_workgroup_1_word", 4, 1)):
+                    cap = timer.capture(lambda i: probe.probe_stream_read(bufs[i % Rf], 1, sink=sink, store_mode=mode,
+                                                                          store_every=ev_), 400, "floor: stores")
+                    if cap is not None:
+                        stores[key] = round(min(timer.replay_us(cap, evict)[0] for _ in range(3)), 3)
+                floor["read_same_bytes_and_store_us"] = stores
+                del bufs, sink
             # what an LDS gather costs: 256 workgroups of 768 lanes that only issue LDS reads;
             # ns per wavefront read and compute unit
             reads, thr = 16000, 768

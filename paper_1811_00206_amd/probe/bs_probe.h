@@ -44,7 +44,10 @@ int bs_probe_wall_clock_khz(void);
  * to consecutive words of `sink` (what a matrix-vector product does with its row sums)
  * with a plain store, a non-temporal store, or an agent-scope atomic store; `sink_bytes`
  * must then cover one word per `store_every` lanes launched (bytes / (16 * pieces_per_lane)
- * lanes, rounded up to whole workgroups of 256) plus one. */
+ * lanes, rounded up to whole workgroups of 256) plus one.  store_mode 4: the first
+ * `store_every` (1..32) lanes of every workgroup store adjacent words of a 128-byte line of
+ * the workgroup's own (32: a whole line in one instruction); `sink` must be 128-byte
+ * aligned for that and hold 128 bytes per workgroup. */
 int bs_probe_stream_read(const void* src, size_t bytes, int pieces_per_lane, int store_mode,
                          int store_every, void* sink, size_t sink_bytes, void* stream);
 

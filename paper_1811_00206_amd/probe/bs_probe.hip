@@ -31,7 +31,8 @@ __global__ void probe_timestamp_kernel(unsigned long long* slot) {
 // value the data cannot produce, so the loads cannot be dropped
 // STORE: 0 = nothing is stored; otherwise one lane in `every` stores its sum to consecutive
 // words (what a matrix-vector product does with its row sums): 1 = a plain store, 2 = a
-// non-temporal store, 3 = an agent-scope atomic store (written through the L2 cache).
+// non-temporal store, 3 = an agent-scope atomic store (written through the L2 cache);
+// 4 = whole or part lines per workgroup (see below).
 template <int U, int STORE>
 __global__ __launch_bounds__(256) void probe_stream_read_kernel(const uint4* __restrict__ src,
                                                                 uint32_t* __restrict__ sink,
@@ -51,6 +52,10 @@ __global__ __launch_bounds__(256) void probe_stream_read_kernel(const uint4* __r
     }
     if constexpr (STORE == 0) {
         if (acc == 0x9e3779b9u && sink) sink[tid & 63] = acc;
+    } else if constexpr (STORE == 4) {
+        // the first `every` lanes (1..32) of every workgroup store adjacent words of the
+        // workgroup's own 128-byte line: with every == 32 a whole line in one instruction
+        if (threadIdx.x < every) sink[(size_t)blockIdx.x * 32 + threadIdx.x] = acc;
     } else if (tid % every == 0) {
         uint32_t* dst = sink + tid / every;
         if constexpr (STORE == 1) *dst = acc;
@@ -207,7 +212,8 @@ int bs_probe_stream_read(const void* src, size_t bytes, int pieces_per_lane, int
     if (pieces_per_lane != 0 && pieces_per_lane != 1 && pieces_per_lane != 2 && pieces_per_lane != 4 &&
         pieces_per_lane != 8)
         return kErrShape;
-    if (store_mode < 0 || store_mode > 3 || (store_mode && store_every < 1)) return kErrShape;
+    if (store_mode < 0 || store_mode > 4 || (store_mode && store_every < 1)) return kErrShape;
+    if (store_mode == 4 && store_every > 32) return kErrShape;
     if (!aligned16(src) || (sink && !aligned16(sink))) return kErrAlign;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t n16 = bytes / 16;
@@ -222,7 +228,8 @@ int bs_probe_stream_read(const void* src, size_t bytes, int pieces_per_lane, int
     if (grid > 65536) grid = 65536;
     if (store_mode) {   // one 4-byte store per `store_every` lanes launched
         if (!sink) return kErrNull;
-        if (sink_bytes < (grid * 256 / (size_t)store_every + 1) * 4) return kErrShape;
+        const size_t words = store_mode == 4 ? grid * 32 : grid * 256 / (size_t)store_every + 1;
+        if (sink_bytes < words * 4) return kErrShape;
     } else if (sink && sink_bytes < 256) {
         return kErrShape;
     }
@@ -233,7 +240,8 @@ int bs_probe_stream_read(const void* src, size_t bytes, int pieces_per_lane, int
         case 0: hipLaunchKernelGGL((probe_stream_read_kernel<UU, 0>), g, b, 0, st, p, s, n16, every); break; \
         case 1: hipLaunchKernelGGL((probe_stream_read_kernel<UU, 1>), g, b, 0, st, p, s, n16, every); break; \
         case 2: hipLaunchKernelGGL((probe_stream_read_kernel<UU, 2>), g, b, 0, st, p, s, n16, every); break; \
-        default: hipLaunchKernelGGL((probe_stream_read_kernel<UU, 3>), g, b, 0, st, p, s, n16, every); break; \
+        case 3: hipLaunchKernelGGL((probe_stream_read_kernel<UU, 3>), g, b, 0, st, p, s, n16, every); break; \
+        default: hipLaunchKernelGGL((probe_stream_read_kernel<UU, 4>), g, b, 0, st, p, s, n16, every); break; \
     }
     switch (u) {
         case 1: BS_PROBE_READ(1) break;
