@@ -639,3 +639,46 @@ def test_graph_replays_match_eager_launches():
         scribble()                                            # eager work between the replays
         g.replay()
         assert snapshot() == eager, f"replay {replay} differs from the eager launches"
+
+
+def test_first_use_inside_a_capture_is_refused_and_init_prevents_it():
+    """The library raises a kernel's LDS limit at its first launch on a device, never while the
+    stream is being captured: a first use inside a capture returns BS_ERR_NOT_INITIALISED (7)
+    and enqueues nothing; after bs_init() the same capture works.  Run in a fresh process (one,
+    on the same GPU), where no kernel has been used yet."""
+    import subprocess
+    import sys
+    code = r'''
+import numpy as np, torch
+from oracle import bs_ref
+from paper_1811_00206_amd import binding as bs, workloads
+dev = "cuda:0"
+W = workloads.draw_weights(64, 25088, 0.01, "f16", 5)          # x of 100 KB: a kernel that needs the raised limit
+x = workloads.draw_activations(25088, 1, 5)
+v, i = bs_ref.prune_pack(W, 64, 6)
+vd, idd, xd = (torch.from_numpy(np.ascontiguousarray(t)).to(dev) for t in (v, i, x))
+y = torch.empty(64, device=dev)
+torch.zeros(1, device=dev); torch.cuda.synchronize()
+def capture():
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        bs.bs_spmv(vd, idd, 64, xd, out=y)
+    return g
+try:
+    capture()
+    print("RESULT first capture unexpectedly worked")
+except bs.BsError as e:
+    print("RESULT refused with status", e.status)
+torch.cuda.synchronize()
+bs.bs_init()
+g = capture()
+y.fill_(0); g.replay(); torch.cuda.synchronize()
+err = bs_ref.rel_l2(y.cpu().numpy(), bs_ref.spmv(v, i, 64, x))
+print("RESULT after init relL2 ok", err <= 1e-2)
+'''
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=240,
+                         cwd=str(__import__("pathlib").Path(__file__).resolve().parent.parent))
+    say(out.stdout[-600:], out.stderr[-600:])
+    lines = [ln for ln in out.stdout.splitlines() if ln.startswith("RESULT")]
+    assert out.returncode == 0, out.stderr[-2000:]
+    assert lines == ["RESULT refused with status 7", "RESULT after init relL2 ok True"], lines
