@@ -103,10 +103,13 @@ __global__ __launch_bounds__(256) void prune_pack_lanes(const VT* __restrict__ W
 
     const int lane = threadIdx.x & (kWave - 1);
     const int q = lane % LPB;
-    const int64_t wave = __builtin_amdgcn_readfirstlane(
-        (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave));
-    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) / kWave;
+    // one group of BPW banks per wavefront, no loop (a loop's invariants, hoisted, cost this
+    // kernel a fifth of its instructions and spilled scalar registers); the grid's second
+    // dimension only extends the workgroup count past 2^20
+    const int64_t wg = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
     const int64_t n_groups = (n_banks + BPW - 1) / BPW;
+    const int64_t grp = wg * (blockDim.x / kWave) + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+    if (grp >= n_groups) return;
     const int pieces = B / E;
 
     // per wavefront: BPW*k value slots and one trash slot per lane, then as many offsets (each
@@ -117,7 +120,7 @@ __global__ __launch_bounds__(256) void prune_pack_lanes(const VT* __restrict__ W
     U* lds_v = reinterpret_cast<U*>(pp_lds + (threadIdx.x / kWave) * (words_v + words_i));
     IT* lds_i = reinterpret_cast<IT*>(reinterpret_cast<uint32_t*>(lds_v) + words_v);
 
-    for (int64_t grp = wave; grp < n_groups; grp += n_waves) {
+    {
         const int64_t g = grp * BPW + lane / LPB;     // this lane's bank
         const bool bank_ok = g < n_banks;
         const Raw* src = reinterpret_cast<const Raw*>(W + (bank_ok ? g : n_banks - 1) * B);
@@ -317,14 +320,15 @@ int launch_shape(const VT* w, VT* v, IT* idx, const IT* remap, int64_t n_banks, 
     } else {
         const int threads = 256;
         const int64_t groups = (n_banks + (kWave / LPB) - 1) / (kWave / LPB);
-        int64_t grid = (groups + threads / kWave - 1) / (threads / kWave);
-        const int64_t cap = 256 * 16;
-        if (grid > cap) grid = cap;
+        const int64_t wgs = (groups + threads / kWave - 1) / (threads / kWave);
+        const int64_t gx = wgs < ((int64_t)1 << 20) ? wgs : ((int64_t)1 << 20);
+        const int64_t gy = (wgs + gx - 1) / gx;
+        if (gy > 65535) return BS_ERR_UNSUPPORTED;
         constexpr int BPW = kWave / LPB;
         const size_t slots = (size_t)BPW * k + kWave;   // the wavefront's output and a trash slot per lane
         const size_t lds = (size_t)(threads / kWave) * 4 *
                            ((slots * sizeof(VT) + 3) / 4 + (slots * sizeof(IT) + 3) / 4);
-        hipLaunchKernelGGL((prune_pack_lanes<VT, IT, PB, LPB, R>), dim3((unsigned)grid), dim3(threads),
+        hipLaunchKernelGGL((prune_pack_lanes<VT, IT, PB, LPB, R>), dim3((unsigned)gx, (unsigned)gy), dim3(threads),
                            lds, st, w, v, idx, remap, n_banks, bank, k);
         return hip_status(hipGetLastError());
     }
