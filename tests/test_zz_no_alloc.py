@@ -45,12 +45,15 @@ def test_static_scratch_matches_workspace_entry_point_twice():
         assert bs_ref.rel_l2(Y_ws.cpu().numpy(), Y_ref) <= tol
         out = torch.full((M, N), float("nan"), device=DEV)
         prepared.append((need, vd, idd, bank, Xd, Y_ws, out))
+        del ws
     assert prepared[0][0] > 0 and prepared[1][0] > 0 and prepared[1][0] < prepared[0][0]
+    import gc
+    gc.collect()
     torch.cuda.synchronize()
     before = torch.cuda.memory_allocated()
     for need, vd, idd, bank, Xd, Y_ws, out in prepared:      # back to back on one stream
         bs.bs_spmm_static(vd, idd, bank, Xd, out)
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_allocated() <= before           # nothing taken from torch's allocator
     torch.cuda.synchronize()
     for n, (need, vd, idd, bank, Xd, Y_ws, out) in enumerate(prepared):
         assert torch.equal(out, Y_ws), f"case {n}: bs_spmm_static differs from bs_spmm"
