@@ -197,3 +197,40 @@ def test_spmm_plan_invariants_random_shapes():
         except b.BsError as e:                       # a documented refusal, never a bad plan
             assert "unsupported" in str(e), (dtype, M, bank * nb, bank, k, N, str(e))
     assert done > 3000
+
+
+def test_spmv_plan_invariants_on_the_paper_shapes_and_random_ones():
+    """What spmv_kernel assumes about its launch, checked on the host: whole wavefronts, a row's
+    lanes inside one wavefront, every row in exactly one workgroup, LDS within a compute unit's."""
+    import random
+    from paper_1811_00206_amd import binding as b
+    rng = random.Random(181100206)
+    shapes = [(b.BS_F32, 256, 256, 64, 16), (b.BS_F32, 6000, 3000, 100, 10), (b.BS_F32, 4096, 4096, 64, 32),
+              (b.BS_F32, 4096, 4096, 64, 2), (b.BS_F16, 4096, 25088, 64, 6), (b.BS_F32, 16384, 8192, 256, 128),
+              (b.BS_F32, 6000, 3000, 25, 10), (b.BS_F32, 4096, 2048, 64, 8), (b.BS_F32, 1, 4, 4, 4)]
+    for _ in range(3000):
+        bank = rng.choice([1, 2, 3, 4, 5, 8, 16, 25, 32, 50, 64, 100, 128, 200, 255, 256])
+        nb = rng.choice([1, 2, 3, 7, 30, 32, 64, 100, 160, 392, 1000])
+        if bank * nb > 40960:
+            continue
+        shapes.append((rng.choice([b.BS_F32, b.BS_F16]), rng.choice([1, 2, 63, 64, 65, 500, 4096, 6000, 16384, 100000]),
+                       bank * nb, bank, rng.randint(1, bank)))
+    for dtype, M, K, bank, k in shapes:
+        p = b.bs_spmv_plan(dtype, M, K, bank, k)
+        where = f"{(dtype, M, K, bank, k)} -> {p}"
+        assert p["slab_kernel"] == 0, where
+        vsize = 2 if dtype == b.BS_F16 else 4
+        row_len = K // bank * k
+        assert p["ch"] in (1, 2, 4, 8) and p["ch"] * vsize <= 16 and row_len % p["ch"] == 0, where
+        assert p["lpr"] in (1, 2, 4, 8, 16, 32, 64) and 2 <= p["u"] <= 8, where
+        assert p["threads"] == p["lpr"] * p["rows_per_wg"] and p["threads"] % 64 == 0 and 64 <= p["threads"] <= 1024, where
+        assert (p["workgroups"] - 1) * p["rows_per_wg"] < M <= p["workgroups"] * p["rows_per_wg"], where
+        x_bytes = (K + 3) // 4 * 16
+        assert p["lds_bytes"] == x_bytes + (row_len * 4 if p["table"] else 0) <= 160 * 1024, where
+        assert p["bank_mode"] == (0 if k % p["ch"] == 0 else 1 if k >= p["ch"] else 2), where
+    # x beyond one compute unit's LDS: the slab kernel, and no launch-shape overrides there
+    assert b.bs_spmv_plan(b.BS_F32, 70, 65536, 256, 16)["slab_kernel"] == 1
+    with pytest.raises(b.BsError):
+        b.bs_spmv_plan(b.BS_F32, 70, 65536, 256, 16, 64, 4)
+    with pytest.raises(b.BsError):
+        b.bs_spmv_plan(b.BS_F32, 64, 256, 64, 16, 3, 0)        # lanes per row not a power of two
