@@ -567,60 +567,64 @@ def main():
         extras["further_trials_us_per_step"] = trials
 
     if not args.no_extras:
-        ev = HipEvents(64)
+        d_us, o_time = float("nan"), roofline.get("empty_launch_us", 0.0)
+        try:                                     # never lose the headline line
+            ev = HipEvents(64)
 
-        def kernel_us_of(v, ix, x, y, bank, n=64):
-            for i in range(n):
-                bs.bs_spmv(v, ix, bank, x, out=y, start_event=ev.pairs[i][0],
-                           stop_event=ev.pairs[i][1])
-            torch.cuda.synchronize()
-            return float(np.median([ev.us(i) for i in range(n)]))
+            def kernel_us_of(v, ix, x, y, bank, n=64):
+                for i in range(n):
+                    bs.bs_spmv(v, ix, bank, x, out=y, start_event=ev.pairs[i][0],
+                               stop_event=ev.pairs[i][1])
+                torch.cuda.synchronize()
+                return float(np.median([ev.us(i) for i in range(n)]))
 
-        # floor of the time-stamp method: a one-row matrix (nothing to stream)
-        v1 = torch.zeros((1, wl.nb, wl.k), dtype=vals.dtype, device=dev)
-        i1 = torch.zeros((1, wl.nb, wl.k), dtype=torch.uint8, device=dev)
-        y1 = torch.empty(1, dtype=torch.float32, device=dev)
-        if not spmm:
-            extras["launch_floor_us"] = round(kernel_us_of(v1, i1, Xd, y1, wl.bank), 2)
-            # the same matrix from cache (one copy): what an LSTM time step loop sees,
-            # in the protocol of `value` (a graph of launches back to back)
-            gw = timer.capture(lambda i: bs.bs_spmv(vals, idx, wl.bank, Xd, out=Y), 64, "warm product")
-            if gw is not None:
-                wg_us = min(timer.replay_us(gw)[0] for _ in range(5))
-                extras["warm_us_per_launch_graph"] = round(wg_us, 3)
-                extras["warm_GBps_per_launch_graph"] = round(alg_bytes / wg_us / 1e3, 1)
-            del gw
+            # floor of the time-stamp method: a one-row matrix (nothing to stream)
+            v1 = torch.zeros((1, wl.nb, wl.k), dtype=vals.dtype, device=dev)
+            i1 = torch.zeros((1, wl.nb, wl.k), dtype=torch.uint8, device=dev)
+            y1 = torch.empty(1, dtype=torch.float32, device=dev)
+            if not spmm:
+                extras["launch_floor_us"] = round(kernel_us_of(v1, i1, Xd, y1, wl.bank), 2)
+                # the same matrix from cache (one copy): what an LSTM time step loop sees,
+                # in the protocol of `value` (a graph of launches back to back)
+                gw = timer.capture(lambda i: bs.bs_spmv(vals, idx, wl.bank, Xd, out=Y), 64, "warm product")
+                if gw is not None:
+                    wg_us = min(timer.replay_us(gw)[0] for _ in range(5))
+                    extras["warm_us_per_launch_graph"] = round(wg_us, 3)
+                    extras["warm_GBps_per_launch_graph"] = round(alg_bytes / wg_us / 1e3, 1)
+                del gw
 
-        # dense baseline on the unpruned-shape matrix, same residency protocol
-        dense_bytes = wl.dense_bytes()
-        Rd = 1 if args.warm else rotation(dense_bytes)
-        Wc = [Wd] + [Wd.clone() for _ in range(Rd - 1)]
-        if spmm:
-            d_us = timer.us(lambda i: bs.bs_dense_gemm(Wc[i % Rd], Xd, out=Y), 20, "dense gemm", evict)
-        else:
-            d_us = timer.us(lambda i: bs.bs_dense_gemv(Wc[i % Rd], Xd, out=Y), 200, "dense gemv", evict)
-        del Wc
-        extras["dense_us"] = round(d_us, 2)
-        extras["dense_GBps"] = round(dense_bytes / d_us / 1e3, 1)
-        extras["speedup_vs_dense"] = round(d_us / us_per_step, 2)   # both: region time per launch
-        # eq. (5) of the paper with the measured dense time and the measured launch floor
-        o_time = roofline.get("empty_launch_us", extras.get("launch_floor_us", 0.0))
-        extras["ideal_us_eq5"] = round((d_us - o_time) * (1 - wl.sparsity) + o_time, 2)
-        # one-time pruning + packing of the dense matrix
-        p_out = (torch.empty_like(vals), torch.empty_like(idx))
-        p_us = timer.us(lambda i: bs.bs_prune_pack(Wd, wl.bank, wl.k, out=p_out), 10, "prune_pack", evict, preroll=2)
-        p_bytes = W.nbytes + wl.nnz * (wl.val_bytes + 1)
-        extras["prune_pack_us"] = round(p_us, 1)
-        extras["prune_pack_GBps"] = round(p_bytes / p_us / 1e3, 1)
-        # one more pruning round on the packed matrix: half the weights of every bank
-        if wl.k >= 2:
-            k2 = wl.k // 2
-            r_out = bs.bs_reprune(vals, idx, wl.bank, k2)
-            r_us = timer.us(lambda i: bs.bs_reprune(vals, idx, wl.bank, k2, out=r_out), 20, "reprune", preroll=2)
-            extras["reprune_to_half_us"] = round(r_us, 1)
-            extras["reprune_GBps"] = round((wl.nnz + wl.M * (wl.K // wl.bank) * k2) *
-                                           (wl.val_bytes + 1) / r_us / 1e3, 1)
-        ev.close()
+            # dense baseline on the unpruned-shape matrix, same residency protocol
+            dense_bytes = wl.dense_bytes()
+            Rd = 1 if args.warm else rotation(dense_bytes)
+            Wc = [Wd] + [Wd.clone() for _ in range(Rd - 1)]
+            if spmm:
+                d_us = timer.us(lambda i: bs.bs_dense_gemm(Wc[i % Rd], Xd, out=Y), 20, "dense gemm", evict)
+            else:
+                d_us = timer.us(lambda i: bs.bs_dense_gemv(Wc[i % Rd], Xd, out=Y), 200, "dense gemv", evict)
+            del Wc
+            extras["dense_us"] = round(d_us, 2)
+            extras["dense_GBps"] = round(dense_bytes / d_us / 1e3, 1)
+            extras["speedup_vs_dense"] = round(d_us / us_per_step, 2)   # both: region time per launch
+            # eq. (5) of the paper with the measured dense time and the measured launch floor
+            o_time = roofline.get("empty_launch_us", extras.get("launch_floor_us", 0.0))
+            extras["ideal_us_eq5"] = round((d_us - o_time) * (1 - wl.sparsity) + o_time, 2)
+            # one-time pruning + packing of the dense matrix
+            p_out = (torch.empty_like(vals), torch.empty_like(idx))
+            p_us = timer.us(lambda i: bs.bs_prune_pack(Wd, wl.bank, wl.k, out=p_out), 10, "prune_pack", evict, preroll=2)
+            p_bytes = W.nbytes + wl.nnz * (wl.val_bytes + 1)
+            extras["prune_pack_us"] = round(p_us, 1)
+            extras["prune_pack_GBps"] = round(p_bytes / p_us / 1e3, 1)
+            # one more pruning round on the packed matrix: half the weights of every bank
+            if wl.k >= 2:
+                k2 = wl.k // 2
+                r_out = bs.bs_reprune(vals, idx, wl.bank, k2)
+                r_us = timer.us(lambda i: bs.bs_reprune(vals, idx, wl.bank, k2, out=r_out), 20, "reprune", preroll=2)
+                extras["reprune_to_half_us"] = round(r_us, 1)
+                extras["reprune_GBps"] = round((wl.nnz + wl.M * (wl.K // wl.bank) * k2) *
+                                               (wl.val_bytes + 1) / r_us / 1e3, 1)
+            ev.close()
+        except Exception as exc:
+            extras["baselines_error"] = str(exc)[:200]
 
         # more of the machine's floor: a large streaming read, LDS gather rates, and the
         # grid-wide barrier a persistent multi-step kernel would need once per step
